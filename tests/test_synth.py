@@ -1,0 +1,66 @@
+"""Seeded input generator: determinism, chunk independence, distribution, bf16 rounding."""
+import numpy as np
+import torch
+
+from paper_2410_01805_amd import synth
+
+
+def test_chunks_are_slices_of_the_stream():
+    w = synth.tiny(N=70, B=16)
+    q, k, v = synth.tokens(w, 0, w.N)
+    for c in range(w.n_chunks):
+        lo, hi = w.chunk_range(c)
+        qc, kc, vc = synth.chunk(w, c)
+        np.testing.assert_array_equal(qc, q[lo:hi])
+        np.testing.assert_array_equal(kc, k[lo:hi])
+        np.testing.assert_array_equal(vc, v[lo:hi])
+    assert w.chunk_range(w.n_chunks - 1) == (64, 70)
+
+
+def test_normal_moments_and_stream_independence():
+    x = synth.standard_normal(3, synth.TID_Q, 0, 400000)
+    y = synth.standard_normal(3, synth.TID_K, 0, 400000)
+    assert abs(x.mean()) < 0.01 and abs(x.std() - 1) < 0.01
+    assert abs(np.mean(x ** 4) - 3.0) < 0.1
+    assert abs(np.corrcoef(x, y)[0, 1]) < 0.01
+    assert abs(np.corrcoef(x[:-1], x[1:])[0, 1]) < 0.01
+    assert not np.array_equal(x, synth.standard_normal(4, synth.TID_Q, 0, 400000))
+
+
+def test_bf16_rounding_matches_library_cast():
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(100000) * 10 ** rng.uniform(-6, 6, 100000)).astype(np.float32)
+    x[:4] = [0.0, -0.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8]      # exact ties round to even
+    mine = synth.bf16_to_f32(synth.bf16_bits(x))
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(mine, lib)
+
+
+def test_workload_table_matches_named_configs():
+    W = synth.WORKLOADS
+    c1, c2, c3, c4, c5 = (W[k] for k in sorted(W))
+    assert (c1.h, c1.h_kv, c1.d, c1.N, c1.B, c1.b, c1.n_s, c1.d_in, c1.d_R) == (8, 2, 64, 4096, 512, 1024, 64, 1536, 256)
+    assert (c2.h, c2.h_kv, c2.d, c2.N, c2.B, c2.b, c2.n_s, c2.d_in, c2.d_R) == (32, 8, 128, 32768, 2048, 6144, 2048, 6144, 1024)
+    assert (c3.N, c3.B, c3.b, c3.n_s, c3.planted_frac, c3.planted_scale) == (131072, 4096, 16384, 2048, 0.01, 4.0)
+    assert (c4.h, c4.h_kv, c4.d, c4.b, c4.n_s, c4.d_in, c4.theta) == (32, 32, 96, 8192, 1024, 9216, 10000.0)
+    assert (c5.N, c5.n_chunks, c5.b, c5.n_s) == (1048576, 256, 8192, 2048)
+
+
+def test_planted_positions_scale_keys_of_all_heads():
+    w = synth.tiny(N=1000, B=100, planted_frac=0.01, planted_scale=4.0)
+    pp = synth.planted_positions(w)
+    assert len(pp) == 10 and len(set(pp.tolist())) == 10
+    base = synth.tiny(N=1000, B=100)
+    _, k0, _ = synth.tokens(base, 0, 1000)
+    _, k1, _ = synth.tokens(w, 0, 1000)
+    ratio = k1 / k0
+    mask = np.zeros(1000, bool); mask[pp] = True
+    np.testing.assert_allclose(ratio[mask], 4.0, rtol=1e-6)
+    np.testing.assert_array_equal(k1[~mask], k0[~mask])
+
+
+def test_weights_std():
+    w = synth.WORKLOADS["cfg1_f32_gqa_4k"]
+    W1, W2 = synth.weights(w)
+    assert W1.shape == (1536, 256) and W2.shape == (256, 2)
+    assert abs(W1.std() - 0.02) < 2e-4
