@@ -1,0 +1,141 @@
+/*
+ * locret.h -- C ABI of the MI355X (gfx950) Locret chunk-step library.
+ *
+ * One attention layer's chunked-prefill step with learned KV-cache eviction
+ * (arXiv 2410.01805): for every incoming chunk
+ *   - attention of the chunk's queries over [retained cache ; chunk], causal inside the chunk
+ *     (Section 3.1, Eq. 1, with the grouped-query head map of Section 3.1);
+ *   - the retaining head  S~ = SiLU([Q,K,V] W1) W2, one score per token per KV head (Section 3.3);
+ *   - stabilizer-masked top-b selection per KV head and order-preserving compaction of
+ *     K, V and score into a fixed-capacity cache (Section 3.4; Appendix A.2, Algorithm 1).
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller and must be 16-byte aligned.
+ *     Only `locret_config*`, `locret_ctx**` and the out-parameters of locret_cache_view are HOST
+ *     pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Compute calls only
+ *     enqueue work on that stream: they never allocate, never synchronise and never read
+ *     results back.  The cache length after a call is known on the host.
+ *   - The workspace is allocated by the caller (locret_workspace_bytes), lent to the context
+ *     for its lifetime and must not be touched while calls are in flight.
+ *   - Return value: 0 (LOCRET_OK) or a negative error code.  Argument errors are found on the
+ *     host before anything is launched and leave the context unchanged.
+ *   - A context is not thread-safe; calls on one context must be issued in stream order.
+ *
+ * Layouts (row-major, innermost last; `s` = element type chosen by config.dtype)
+ *   q            [T][n_q_heads][head_dim]   s    un-rotated
+ *   k, v         [T][n_kv_heads][head_dim]  s    un-rotated
+ *   attn_out     [T][n_q_heads][head_dim]   s
+ *   scores       [n_kv_heads][T]            float
+ *   kept_idx     [n_kv_heads][budget]       int32; the first n_keep entries of each row are valid
+ *   W1           [d_in][d_hidden]           s
+ *   W2           [d_hidden][n_kv_heads]     s
+ */
+#ifndef LOCRET_H
+#define LOCRET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LOCRET_OK        0
+#define LOCRET_EINVAL   -1   /* NULL pointer or a value outside its domain                 */
+#define LOCRET_ESHAPE   -2   /* unsupported head layout / sizes, or T outside 1..chunk_max */
+#define LOCRET_EALIGN   -3   /* a device pointer is not 16-byte aligned                    */
+#define LOCRET_ESTATE   -4   /* call not valid in the context's state (weights missing,
+                                cache would overflow its capacity)                         */
+#define LOCRET_EHIP     -5   /* the HIP runtime reported an error                          */
+#define LOCRET_ENOMEM   -6   /* workspace too small / host allocation failed               */
+
+#define LOCRET_F32   0
+#define LOCRET_BF16  1
+
+typedef struct locret_ctx locret_ctx;   /* opaque host-side handle */
+
+/* Problem statement of Algorithm 1 (budget b, chunk size B) plus the head layout of Section 3.1. */
+typedef struct {
+  int32_t n_q_heads;      /* h                                                                 */
+  int32_t n_kv_heads;     /* h/g; must divide n_q_heads                                        */
+  int32_t head_dim;       /* d: 64, 96 or 128 on the bf16 path; any multiple of 8 up to 128 in f32 */
+  int32_t chunk_max;      /* B: largest T of any call                                          */
+  int32_t budget;         /* b: cache units kept per KV head                                   */
+  int32_t d_hidden;       /* d_R: retaining-head hidden width (multiple of 128 in bf16, 16 in f32) */
+  int32_t rh_kv_expand;   /* 0: W1 has (h + 2 h/g) d rows, the shape Section 3.3 states
+                             1: W1 has 3 h d rows; the K and V blocks are repeated g times in
+                                query-head order (query head j reads KV head floor(j/g))      */
+  int32_t dtype;          /* LOCRET_F32 or LOCRET_BF16: type of q, k, v, W1, W2, out and cache */
+  int32_t rope_mode;      /* 0: no rotary embedding
+                             1: K is cached un-rotated; at every call cache slot i is rotated to
+                                position i and chunk token t (key and query) to n_c + t
+                                (Section 3.4; pairs (i, i + d/2), inverse frequency theta^(-2i/d)) */
+  float   rope_theta;
+  float   softmax_scale;  /* 0 selects 1/sqrt(head_dim)                                        */
+} locret_config;
+
+/* Bytes of device workspace a context needs (both cache copies, rotated-key shadow, score and
+ * position arrays, weights in kernel layout, scratch).  0 if the config is invalid. */
+size_t locret_workspace_bytes(const locret_config* cfg);
+
+/* Validates cfg, takes the workspace (device, 256-byte aligned, >= locret_workspace_bytes) and
+ * builds the rotary table.  Synchronises the device once.  *out is set only on success. */
+int locret_create(const locret_config* cfg, void* dev_workspace, size_t workspace_bytes, locret_ctx** out);
+
+/* Copies the retaining head's weights into the workspace in the layout the kernels use
+ * (W1 transposed; with rh_kv_expand = 1 the g repeated row blocks are summed, which is the same
+ * linear map).  W1, W2: device, layouts above.  Asynchronous on `stream`. */
+int locret_set_weights(locret_ctx* ctx, const void* W1, const void* W2, void* stream);
+
+/* Empties the cache (n_c = 0, tokens seen = 0).  Host-only. */
+int locret_reset(locret_ctx* ctx);
+
+/* The whole chunk step (Algorithm 1's loop body for one layer) for T tokens, 1 <= T <= chunk_max:
+ *   attention -> attn_out; retaining head -> scores; append; if `evict` != 0: keep the last
+ *   min(n_stab, n_c + T) units plus the best of the others up to `budget`, compact.
+ * n_stab     stabilizer length n_s for this call, 0 <= n_stab <= budget (Algorithm 1 passes 0 on
+ *            the last chunk).
+ * evict      0 = append only (the trailing n_loc pass of Algorithm 1); needs n_c + T <= budget +
+ *            chunk_max, else LOCRET_ESTATE.
+ * scores_in  NULL, or float [n_kv_heads][T]: use these scores for the selection instead of the
+ *            retaining head's (the retaining head still runs and fills scores_out).
+ * scores_out NULL or float [n_kv_heads][T].
+ * kept_idx_out NULL or int32 [n_kv_heads][budget]: kept indices, ascending, in the concatenated
+ *            index space (i < n_c: old cache slot i; otherwise chunk token i - n_c); row m holds
+ *            n_keep = min(n_c + T, budget) valid entries (all n_c + T when evict = 0 is not
+ *            reported: kept_idx_out is left untouched then).
+ * Selection order: score descending, then index ascending; -0 == +0; NaN below every number. */
+int locret_prefill_chunk(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t T,
+                         int32_t n_stab, int32_t evict, const float* scores_in, void* attn_out,
+                         float* scores_out, int32_t* kept_idx_out, void* stream);
+
+/* Retaining head alone (Section 3.3): scores[m][t] for T tokens; the cache is not touched. */
+int locret_score(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t T,
+                 float* scores, void* stream);
+
+/* Append + stabilizer-masked top-b + compaction alone (Section 3.4, Algorithm 1) on caller-supplied
+ * scores [n_kv_heads][T]; arguments as in locret_prefill_chunk. */
+int locret_evict_compact(locret_ctx* ctx, const float* chunk_scores, const void* k_chunk,
+                         const void* v_chunk, int32_t T, int32_t n_stab, int32_t* kept_idx_out,
+                         void* stream);
+
+/* Units currently in the cache per KV head (same for every head), and tokens seen so far. */
+int32_t locret_cache_len(const locret_ctx* ctx);
+int64_t locret_tokens_seen(const locret_ctx* ctx);
+
+/* Device pointers into the workspace for the live cache copy: K, V [n_kv_heads][row_stride][head_dim]
+ * (un-rotated), score [n_kv_heads][row_stride] float, orig_pos [n_kv_heads][row_stride] int32
+ * (absolute token index of each unit; bookkeeping only).  Valid until the next call that
+ * evicts.  Any out-pointer may be NULL. */
+int locret_cache_view(const locret_ctx* ctx, const void** K, const void** V, const float** score,
+                      const int32_t** orig_pos, int32_t* len, int32_t* row_stride);
+
+void locret_destroy(locret_ctx* ctx);
+
+const char* locret_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOCRET_H */

@@ -1,0 +1,288 @@
+// Host side of the C ABI declared in include/locret.h: argument checks, workspace layout, cache
+// bookkeeping (all host-known, no readbacks) and the per-chunk launch sequence.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/locret.h"
+#include "kernels.h"
+
+using namespace locret;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+  size_t K[2], V[2], Kr[2], S[2], P[2];
+  size_t qr, tab, W1t, W2f, part, kept, total;
+};
+
+bool valid_head_dim(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
+
+int validate(const locret_config* c) {
+  if (!c) return LOCRET_EINVAL;
+  if (c->dtype != LOCRET_F32 && c->dtype != LOCRET_BF16) return LOCRET_EINVAL;
+  if (c->rope_mode != 0 && c->rope_mode != 1) return LOCRET_EINVAL;
+  if (c->rh_kv_expand != 0 && c->rh_kv_expand != 1) return LOCRET_EINVAL;
+  if (c->rope_mode == 1 && !(c->rope_theta > 0.f && isfinite(c->rope_theta))) return LOCRET_EINVAL;
+  if (!(c->softmax_scale >= 0.f) || !isfinite(c->softmax_scale)) return LOCRET_EINVAL;
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->chunk_max < 1 || c->budget < 1 || c->d_hidden < 1)
+    return LOCRET_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0) return LOCRET_ESHAPE;
+  if (!valid_head_dim(c->head_dim)) return LOCRET_ESHAPE;
+  if (c->n_q_heads > 1024 || c->d_hidden > 65536) return LOCRET_ESHAPE;
+  if ((int64_t)c->budget + c->chunk_max > (int64_t)1 << 28) return LOCRET_ESHAPE;
+  return LOCRET_OK;
+}
+
+void fill_dims(const locret_config* c, Dims* D) {
+  D->h = c->n_q_heads;
+  D->h_kv = c->n_kv_heads;
+  D->g = D->h / D->h_kv;
+  D->d = c->head_dim;
+  D->cap = c->budget + c->chunk_max;
+  D->bf16 = c->dtype == LOCRET_BF16;
+  D->rope = c->rope_mode;
+  D->K = (D->h + 2 * D->h_kv) * D->d;
+  D->d_R = c->d_hidden;
+}
+
+int max_score_parts(const Dims& D) {
+  int a = score_parts_simple(D), b = score_parts_bf16(D);
+  return a > b ? a : b;
+}
+
+void make_layout(const locret_config* c, const Dims& D, Layout* L) {
+  const size_t es = D.bf16 ? 2 : 4;
+  const size_t rows = (size_t)D.h_kv * D.cap;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
+  for (int i = 0; i < 2; ++i) {
+    L->K[i] = take(rows * D.d * es);
+    L->V[i] = take(rows * D.d * es);
+    L->Kr[i] = D.rope ? take(rows * D.d * es) : 0;
+    L->S[i] = take(rows * sizeof(float));
+    L->P[i] = take(rows * sizeof(int32_t));
+  }
+  L->qr = D.rope ? take((size_t)c->chunk_max * D.h * D.d * es) : 0;
+  L->tab = D.rope ? take((size_t)D.cap * (D.d / 2) * sizeof(float2)) : 0;
+  L->W1t = take((size_t)D.d_R * D.K * es);
+  L->W2f = take((size_t)D.d_R * D.h_kv * sizeof(float));
+  L->part = take((size_t)max_score_parts(D) * D.h_kv * c->chunk_max * sizeof(float));
+  L->kept = take((size_t)D.h_kv * c->budget * sizeof(int32_t));
+  L->total = off;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+struct locret_ctx {
+  locret_config cfg;
+  Dims D;
+  Layout L;
+  char* ws;
+  int cur;          // live cache copy
+  int n_c;          // units per head in the live copy
+  int64_t seen;     // tokens appended so far
+  int have_weights;
+  float scale;
+  int mfma_attn, mfma_score;
+  CacheBuf buf(int i) const {
+    CacheBuf b;
+    b.K = ws + L.K[i];
+    b.V = ws + L.V[i];
+    b.Kr = D.rope ? ws + L.Kr[i] : nullptr;
+    b.S = (float*)(ws + L.S[i]);
+    b.P = (int32_t*)(ws + L.P[i]);
+    return b;
+  }
+};
+
+extern "C" {
+
+size_t locret_workspace_bytes(const locret_config* cfg) {
+  if (validate(cfg) != LOCRET_OK) return 0;
+  Dims D;
+  fill_dims(cfg, &D);
+  Layout L;
+  make_layout(cfg, D, &L);
+  return L.total;
+}
+
+int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx** out) {
+  if (!out) return LOCRET_EINVAL;
+  int rc = validate(cfg);
+  if (rc != LOCRET_OK) return rc;
+  if (!ws) return LOCRET_EINVAL;
+  if (((uintptr_t)ws & (ALIGN - 1)) != 0) return LOCRET_EALIGN;
+  locret_ctx* c = new (std::nothrow) locret_ctx;
+  if (!c) return LOCRET_ENOMEM;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  fill_dims(cfg, &c->D);
+  make_layout(cfg, c->D, &c->L);
+  if (bytes < c->L.total) { delete c; return LOCRET_ENOMEM; }
+  c->ws = (char*)ws;
+  c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  const char* force = getenv("LOCRET_FORCE_SIMPLE");
+  const bool simple = force && force[0] == '1';
+  const int d = cfg->head_dim;
+  c->mfma_attn = !simple && c->D.bf16 && (d == 64 || d == 96 || d == 128);
+  c->mfma_score = !simple && c->D.bf16 && score_parts_bf16(c->D) > 0;
+  if (c->D.rope) {
+    launch_rope_table((float2*)(c->ws + c->L.tab), c->D.cap, c->D.d, cfg->rope_theta, 0);
+    if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) { delete c; return LOCRET_EHIP; }
+  } else if (hipDeviceSynchronize() != hipSuccess) {   // also proves a device is usable
+    (void)hipGetLastError();
+    delete c;
+    return LOCRET_EHIP;
+  }
+  *out = c;
+  return LOCRET_OK;
+}
+
+int locret_set_weights(locret_ctx* c, const void* W1, const void* W2, void* stream) {
+  if (!c || !W1 || !W2) return LOCRET_EINVAL;
+  if (misaligned(W1) || misaligned(W2)) return LOCRET_EALIGN;
+  launch_prep_weights(c->D, c->cfg.rh_kv_expand, W1, W2, c->ws + c->L.W1t, (float*)(c->ws + c->L.W2f),
+                      (hipStream_t)stream);
+  if (hipGetLastError() != hipSuccess) return LOCRET_EHIP;
+  c->have_weights = 1;
+  return LOCRET_OK;
+}
+
+int locret_reset(locret_ctx* c) {
+  if (!c) return LOCRET_EINVAL;
+  c->n_c = 0;
+  c->seen = 0;
+  return LOCRET_OK;
+}
+
+static void run_score(locret_ctx* c, const void* q, const void* k, const void* v, int T, float* S_dst, int n_c,
+                      float* out, hipStream_t st) {
+  float* part = (float*)(c->ws + c->L.part);
+  int parts;
+  if (c->mfma_score) {
+    launch_score_bf16(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
+    parts = score_parts_bf16(c->D);
+  } else {
+    launch_score_simple(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
+    parts = score_parts_simple(c->D);
+  }
+  launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st);
+}
+
+// select + compact on the live copy, whose rows [0, L) are filled; updates the host bookkeeping
+static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, hipStream_t st) {
+  const int b = c->cfg.budget;
+  const int n_keep = L < b ? L : b;
+  const int ns = n_stab < L ? n_stab : L;
+  CacheBuf A = c->buf(c->cur);
+  int32_t* kept = (int32_t*)(c->ws + c->L.kept);
+  launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, kept, b, kept_idx_out, b, st);
+  if (L > b) {
+    CacheBuf B = c->buf(c->cur ^ 1);
+    launch_compact(c->D, A, B, kept, b, n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
+    c->cur ^= 1;
+  }
+  c->n_c = n_keep;
+}
+
+int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, int32_t n_stab,
+                         int32_t evict, const float* scores_in, void* attn_out, float* scores_out,
+                         int32_t* kept_idx_out, void* stream) {
+  if (!c || !q || !k || !v || !attn_out) return LOCRET_EINVAL;
+  if (n_stab < 0 || n_stab > c->cfg.budget) return LOCRET_EINVAL;
+  if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(attn_out) || misaligned(scores_in) ||
+      misaligned(scores_out) || misaligned(kept_idx_out))
+    return LOCRET_EALIGN;
+  if (!c->have_weights) return LOCRET_ESTATE;
+  if (c->n_c + T > c->D.cap) return LOCRET_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  const Dims& D = c->D;
+  CacheBuf A = c->buf(c->cur);
+  const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
+  void* qr = D.rope ? c->ws + c->L.qr : nullptr;
+
+  launch_append(D, q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
+  const void* qx = D.rope ? qr : q;
+  const void* Kx = D.rope ? A.Kr : A.K;
+  if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
+  else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
+  run_score(c, q, k, v, T, scores_in ? nullptr : A.S, c->n_c, scores_out, st);
+  if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st);
+
+  const int L = c->n_c + T;
+  if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
+  else c->n_c = L;
+  c->seen += T;
+  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
+}
+
+int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, float* scores,
+                 void* stream) {
+  if (!c || !q || !k || !v || !scores) return LOCRET_EINVAL;
+  if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(scores)) return LOCRET_EALIGN;
+  if (!c->have_weights) return LOCRET_ESTATE;
+  run_score(c, q, k, v, T, nullptr, 0, scores, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
+}
+
+int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k, const void* v, int32_t T,
+                         int32_t n_stab, int32_t* kept_idx_out, void* stream) {
+  if (!c || !chunk_scores || !k || !v) return LOCRET_EINVAL;
+  if (n_stab < 0 || n_stab > c->cfg.budget) return LOCRET_EINVAL;
+  if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
+  if (misaligned(chunk_scores) || misaligned(k) || misaligned(v) || misaligned(kept_idx_out)) return LOCRET_EALIGN;
+  if (c->n_c + T > c->D.cap) return LOCRET_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  const Dims& D = c->D;
+  CacheBuf A = c->buf(c->cur);
+  const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
+  launch_append(D, nullptr, k, v, T, c->n_c, c->seen, A, nullptr, tab, st);
+  launch_score_reduce(chunk_scores, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st);
+  run_evict(c, c->n_c + T, n_stab, kept_idx_out, st);
+  c->seen += T;
+  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
+}
+
+int32_t locret_cache_len(const locret_ctx* c) { return c ? c->n_c : LOCRET_EINVAL; }
+int64_t locret_tokens_seen(const locret_ctx* c) { return c ? c->seen : (int64_t)LOCRET_EINVAL; }
+
+int locret_cache_view(const locret_ctx* c, const void** K, const void** V, const float** score,
+                      const int32_t** orig_pos, int32_t* len, int32_t* row_stride) {
+  if (!c) return LOCRET_EINVAL;
+  CacheBuf A = c->buf(c->cur);
+  if (K) *K = A.K;
+  if (V) *V = A.V;
+  if (score) *score = A.S;
+  if (orig_pos) *orig_pos = A.P;
+  if (len) *len = c->n_c;
+  if (row_stride) *row_stride = c->D.cap;
+  return LOCRET_OK;
+}
+
+void locret_destroy(locret_ctx* c) { delete c; }
+
+const char* locret_strerror(int code) {
+  switch (code) {
+    case LOCRET_OK: return "ok";
+    case LOCRET_EINVAL: return "invalid argument (null pointer or value outside its domain)";
+    case LOCRET_ESHAPE: return "unsupported shape (head layout, head_dim, or T outside 1..chunk_max)";
+    case LOCRET_EALIGN: return "device pointer not 16-byte aligned (workspace: 256-byte)";
+    case LOCRET_ESTATE: return "call not valid in this state (weights not set, or cache capacity exceeded)";
+    case LOCRET_EHIP: return "HIP runtime error";
+    case LOCRET_ENOMEM: return "workspace too small or host allocation failed";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

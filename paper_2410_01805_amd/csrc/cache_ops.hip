@@ -1,0 +1,217 @@
+// Bandwidth-bound cache maintenance kernels for gfx950: rotary table, weight preparation,
+// chunk append (Algorithm 1 "Concat") and order-preserving compaction (Algorithm 1 gather).
+// Every thread moves 16-byte vectors; a row of d elements is shared by (d/2)/VEC threads, each of
+// which owns VEC rotary pairs (i, i + d/2), so the rotated shadow of K is produced from registers.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace locret {
+
+// ------------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(float2* tab, int cap, int half, int d, double theta) {
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)cap * half) return;
+  int pos = (int)(gid / half), i = (int)(gid % half);
+  double inv = pow(theta, -2.0 * (double)i / (double)d);
+  double a = (double)pos * inv;
+  tab[gid] = make_float2((float)cos(a), (float)sin(a));
+}
+
+void launch_rope_table(float2* tab, int cap, int d, float theta, hipStream_t st) {
+  int64_t n = (int64_t)cap * (d / 2);
+  int blocks = (int)((n + 255) / 256);
+  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks), dim3(256), 0, st, tab, cap, d / 2, d, (double)theta);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void prep_w1_kernel(const T* __restrict__ W1, T* __restrict__ W1t, int h, int h_kv, int g, int d,
+                               int d_R, int K, int expand) {
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)K * d_R) return;
+  int n = (int)(gid % d_R);
+  int c = (int)(gid / d_R);
+  int hd = h * d;
+  float acc;
+  if (!expand || c < hd) {
+    acc = Elem<T>::ld(W1 + (int64_t)c * d_R + n);
+  } else {
+    int cc = c - hd;
+    int blk = cc / (h_kv * d);          // 0: K block, 1: V block
+    int r = cc % (h_kv * d);
+    int m = r / d, i = r % d;
+    int64_t base = (int64_t)hd * (1 + blk);
+    acc = 0.f;
+    for (int rep = 0; rep < g; ++rep)
+      acc += Elem<T>::ld(W1 + (base + (int64_t)(m * g + rep) * d + i) * d_R + n);
+  }
+  Elem<T>::st(W1t + (int64_t)n * K + c, acc);
+}
+
+template <typename T>
+__global__ void prep_w2_kernel(const T* __restrict__ W2, float* __restrict__ W2f, int n) {
+  int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid < n) W2f[gid] = Elem<T>::ld(W2 + gid);
+}
+
+void launch_prep_weights(const Dims& D, int expand, const void* W1, const void* W2, void* W1t, float* W2f,
+                         hipStream_t st) {
+  int64_t n1 = (int64_t)D.K * D.d_R;
+  int n2 = D.d_R * D.h_kv;
+  dim3 b1((unsigned)((n1 + 255) / 256)), b2((unsigned)((n2 + 255) / 256));
+  if (D.bf16) {
+    hipLaunchKernelGGL(prep_w1_kernel<bf16_t>, b1, dim3(256), 0, st, (const bf16_t*)W1, (bf16_t*)W1t, D.h,
+                       D.h_kv, D.g, D.d, D.d_R, D.K, expand);
+    hipLaunchKernelGGL(prep_w2_kernel<bf16_t>, b2, dim3(256), 0, st, (const bf16_t*)W2, W2f, n2);
+  } else {
+    hipLaunchKernelGGL(prep_w1_kernel<float>, b1, dim3(256), 0, st, (const float*)W1, (float*)W1t, D.h,
+                       D.h_kv, D.g, D.d, D.d_R, D.K, expand);
+    hipLaunchKernelGGL(prep_w2_kernel<float>, b2, dim3(256), 0, st, (const float*)W2, W2f, n2);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// rotate VEC pairs held as (lo, hi) by the table row of `pos`
+template <typename T>
+__device__ __forceinline__ void rotate_pairs(const Vec16<T>& lo, const Vec16<T>& hi, Vec16<T>& olo, Vec16<T>& ohi,
+                                             const float2* __restrict__ tab_row) {
+#pragma unroll
+  for (int i = 0; i < Vec16<T>::N; ++i) {
+    float2 cs = tab_row[i];
+    float a = lo.get(i), b = hi.get(i);
+    olo.set(i, a * cs.x - b * cs.y);
+    ohi.set(i, b * cs.x + a * cs.y);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                     const T* __restrict__ v, int Tn, int n_c, int seen, int h,
+                                                     int h_kv, int d, int cap, T* __restrict__ Kc,
+                                                     T* __restrict__ Vc, T* __restrict__ Krc,
+                                                     int32_t* __restrict__ Pc, T* __restrict__ qr,
+                                                     const float2* __restrict__ tab, int rope, int q_rows) {
+  constexpr int VEC = Vec16<T>::N;
+  const int half = d / 2;
+  const int tpr = half / VEC;
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t row = gid / tpr;
+  int part = (int)(gid % tpr);
+  const int rows_per_tok = q_rows + 2 * h_kv;   // q_rows = h when queries are rotated here, else 0
+  if (row >= (int64_t)Tn * rows_per_tok) return;
+  int t = (int)(row / rows_per_tok);
+  int r = (int)(row % rows_per_tok);
+  int off = part * VEC;
+  typedef Vec16<T> V16;
+  if (r < q_rows) {
+    const T* src = q + ((int64_t)t * h + r) * d;
+    V16 lo, hi, olo, ohi;
+    lo.raw = *(const decltype(lo.raw)*)(src + off);
+    hi.raw = *(const decltype(hi.raw)*)(src + half + off);
+    rotate_pairs<T>(lo, hi, olo, ohi, tab + (int64_t)(n_c + t) * half + off);
+    T* dst = qr + ((int64_t)t * h + r) * d;
+    *(decltype(lo.raw)*)(dst + off) = olo.raw;
+    *(decltype(lo.raw)*)(dst + half + off) = ohi.raw;
+    return;
+  }
+  r -= q_rows;
+  const bool is_k = r < h_kv;
+  int m = is_k ? r : r - h_kv;
+  const T* src = (is_k ? k : v) + ((int64_t)t * h_kv + m) * d;
+  V16 lo, hi;
+  lo.raw = *(const decltype(lo.raw)*)(src + off);
+  hi.raw = *(const decltype(hi.raw)*)(src + half + off);
+  int64_t drow = ((int64_t)m * cap + n_c + t) * d;
+  T* dst = (is_k ? Kc : Vc) + drow;
+  *(decltype(lo.raw)*)(dst + off) = lo.raw;
+  *(decltype(lo.raw)*)(dst + half + off) = hi.raw;
+  if (is_k) {
+    if (rope) {
+      V16 olo, ohi;
+      rotate_pairs<T>(lo, hi, olo, ohi, tab + (int64_t)(n_c + t) * half + off);
+      *(decltype(lo.raw)*)(Krc + drow + off) = olo.raw;
+      *(decltype(lo.raw)*)(Krc + drow + half + off) = ohi.raw;
+    }
+    if (part == 0) Pc[(int64_t)m * cap + n_c + t] = seen + t;
+  }
+}
+
+void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c, int64_t seen,
+                   const CacheBuf& c, void* qr, const float2* tab, hipStream_t st) {
+  const int vec = D.bf16 ? 8 : 4;
+  const int tpr = (D.d / 2) / vec;
+  const int q_rows = (D.rope && q != nullptr) ? D.h : 0;
+  int64_t threads = (int64_t)T * (q_rows + 2 * D.h_kv) * tpr;
+  dim3 grid((unsigned)((threads + 255) / 256));
+  if (D.bf16)
+    hipLaunchKernelGGL(append_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (bf16_t*)c.K, (bf16_t*)c.V,
+                       (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows);
+  else
+    hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
+                       (const float*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (float*)c.K, (float*)c.V,
+                       (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                      const float* __restrict__ Ss, const int32_t* __restrict__ Ps,
+                                                      T* __restrict__ Kd, T* __restrict__ Vd, T* __restrict__ Krd,
+                                                      float* __restrict__ Sd, int32_t* __restrict__ Pd,
+                                                      const int32_t* __restrict__ kept, int kept_stride,
+                                                      int n_keep, int h_kv, int d, int cap,
+                                                      const float2* __restrict__ tab, int rope) {
+  constexpr int VEC = Vec16<T>::N;
+  const int half = d / 2;
+  const int tpr = half / VEC;
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t row = gid / tpr;
+  int part = (int)(gid % tpr);
+  if (row >= (int64_t)h_kv * n_keep) return;
+  int m = (int)(row / n_keep);
+  int r = (int)(row % n_keep);
+  int src = kept[(int64_t)m * kept_stride + r];
+  int off = part * VEC;
+  int64_t srow = ((int64_t)m * cap + src) * d;
+  int64_t drow = ((int64_t)m * cap + r) * d;
+  typedef Vec16<T> V16;
+  V16 klo, khi, vlo, vhi;
+  klo.raw = *(const decltype(klo.raw)*)(Ks + srow + off);
+  khi.raw = *(const decltype(klo.raw)*)(Ks + srow + half + off);
+  vlo.raw = *(const decltype(klo.raw)*)(Vs + srow + off);
+  vhi.raw = *(const decltype(klo.raw)*)(Vs + srow + half + off);
+  *(decltype(klo.raw)*)(Kd + drow + off) = klo.raw;
+  *(decltype(klo.raw)*)(Kd + drow + half + off) = khi.raw;
+  *(decltype(klo.raw)*)(Vd + drow + off) = vlo.raw;
+  *(decltype(klo.raw)*)(Vd + drow + half + off) = vhi.raw;
+  if (rope) {
+    V16 olo, ohi;
+    rotate_pairs<T>(klo, khi, olo, ohi, tab + (int64_t)r * half + off);
+    *(decltype(klo.raw)*)(Krd + drow + off) = olo.raw;
+    *(decltype(klo.raw)*)(Krd + drow + half + off) = ohi.raw;
+  }
+  if (part == 0) {
+    Sd[(int64_t)m * cap + r] = Ss[(int64_t)m * cap + src];
+    Pd[(int64_t)m * cap + r] = Ps[(int64_t)m * cap + src];
+  }
+}
+
+void launch_compact(const Dims& D, const CacheBuf& s, const CacheBuf& t, const int32_t* kept, int kept_stride,
+                    int n_keep, const float2* tab, hipStream_t st) {
+  const int vec = D.bf16 ? 8 : 4;
+  const int tpr = (D.d / 2) / vec;
+  int64_t threads = (int64_t)D.h_kv * n_keep * tpr;
+  if (threads == 0) return;
+  dim3 grid((unsigned)((threads + 255) / 256));
+  if (D.bf16)
+    hipLaunchKernelGGL(compact_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)s.K, (const bf16_t*)s.V, s.S,
+                       s.P, (bf16_t*)t.K, (bf16_t*)t.V, (bf16_t*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv,
+                       D.d, D.cap, tab, D.rope);
+  else
+    hipLaunchKernelGGL(compact_kernel<float>, grid, dim3(256), 0, st, (const float*)s.K, (const float*)s.V, s.S,
+                       s.P, (float*)t.K, (float*)t.V, (float*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv,
+                       D.d, D.cap, tab, D.rope);
+}
+
+}  // namespace locret

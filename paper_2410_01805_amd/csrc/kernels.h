@@ -1,0 +1,74 @@
+// Internal launch interface between the C-ABI host code (api.hip) and the gfx950 kernels.
+// Not part of the public boundary (include/locret.h is).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace locret {
+
+struct Dims {
+  int h;        // query heads
+  int h_kv;     // KV heads
+  int g;        // h / h_kv
+  int d;        // head dim
+  int cap;      // rows per KV head in every cache array (budget + chunk_max)
+  int bf16;     // 0: float storage, 1: bf16 storage
+  int rope;     // rotary mode
+  int K;        // retaining-head input width after folding: (h + 2 h_kv) d
+  int d_R;      // retaining-head hidden width
+};
+
+// One copy of the cache (the library ping-pongs between two).
+struct CacheBuf {
+  void* K;       // [h_kv][cap][d] un-rotated keys
+  void* V;       // [h_kv][cap][d]
+  void* Kr;      // [h_kv][cap][d] keys rotated to their slot position (rope only, else NULL)
+  float* S;      // [h_kv][cap] true scores
+  int32_t* P;    // [h_kv][cap] original token index
+};
+
+// tab[pos][i] = (cos, sin)(pos * theta^(-2i/d)), angles formed in double.
+void launch_rope_table(float2* tab, int cap, int d, float theta, hipStream_t st);
+
+// Weight preparation (Section 3.3).  W1t [d_R][K]: transpose of W1 with the g repeated K/V row
+// blocks summed when `expand`; W2f [d_R][h_kv] float.
+void launch_prep_weights(const Dims& D, int expand, const void* W1, const void* W2, void* W1t,
+                         float* W2f, hipStream_t st);
+
+// Append the chunk at slots [n_c, n_c+T) of `c`: K, V copied, Kr = K rotated to n_c+t,
+// P = seen + t; qr [T][h][d] = q rotated to n_c+t (rope only; q may be NULL to skip).
+void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c,
+                   int64_t seen, const CacheBuf& c, void* qr, const float2* tab, hipStream_t st);
+
+// Attention of T queries (already rotated if rope) over slots [0, n_c+T) of Kx/V, query t seeing
+// slots <= n_c+t (Eq. 1).  Reference-grade VALU kernel, any storage type.
+void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
+                             int T, int n_c, float scale, hipStream_t st);
+// bf16 MFMA kernel (d in {64, 96, 128}).
+void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
+                           int T, int n_c, float scale, hipStream_t st);
+
+// Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
+// blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
+int score_parts_simple(const Dims& D);
+int score_parts_bf16(const Dims& D);
+void launch_score_simple(const Dims& D, const void* q, const void* k, const void* v, int T,
+                         const void* W1t, const float* W2f, float* part, hipStream_t st);
+void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T,
+                       const void* W1t, const float* W2f, float* part, hipStream_t st);
+// scores[m][t] = sum over nb (fixed order) -> S[m*cap + n_c + t] (if S) and out[m*T + t] (if out).
+// With n_parts == 1 this is a strided copy (used for caller-supplied scores).
+void launch_score_reduce(const float* part, int n_parts, int part_stride_T, int h_kv, int T, float* S,
+                         int cap, int n_c, float* out, hipStream_t st);
+
+// Stabilizer-masked top-k per KV head over S[m][0..L): keeps the last n_stab and the best
+// (n_keep - n_stab) of the rest (score desc, index asc); kept[m][0..n_keep) ascending.
+// kept2 (optional, row stride stride2) receives a copy.
+void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int32_t* kept,
+                   int kept_stride, int32_t* kept2, int stride2, hipStream_t st);
+
+// dst[m][r] = src[m][kept[m][r]] for K, V, S, P; dst.Kr[m][r] = K rotated to position r.
+void launch_compact(const Dims& D, const CacheBuf& src, const CacheBuf& dst, const int32_t* kept,
+                    int kept_stride, int n_keep, const float2* tab, hipStream_t st);
+
+}  // namespace locret

@@ -1,0 +1,162 @@
+// Stabilizer-masked top-k per KV head (Section 3.4; Algorithm 1: "+inf on the last n_s, top-b").
+//
+// One 1024-thread workgroup per KV head.  Scores become order-preserving 32-bit keys (NaN lowest,
+// -0 == +0) held in LDS; a 4-pass, 8-bit-per-pass radix select finds the key tau of the k-th best
+// candidate and how many units equal to tau still fit; a ballot-based ordered compaction then emits
+// the kept indices ascending, taking equal keys from the lowest index up.  Integer work only, so
+// the result is exact and deterministic.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace locret {
+
+__device__ __forceinline__ uint32_t score_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN: below every number
+  if (u == 0x80000000u) u = 0u;                     // -0 ties with +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_HDR = 384;   // words of LDS before the keys: hist[256] wsum[64] bc[64]
+
+template <bool IN_LDS>
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ S, int cap, int L,
+                                                             int n_keep, int n_stab, int32_t* __restrict__ kept,
+                                                             int kept_stride, int32_t* __restrict__ kept2,
+                                                             int stride2) {
+  extern __shared__ uint32_t smem[];
+  uint32_t* hist = smem;
+  uint32_t* wsum = smem + 256;
+  uint32_t* bc = smem + 320;
+  uint32_t* keys = smem + SEL_HDR;
+
+  const int m = blockIdx.x;
+  const float* s = S + (int64_t)m * cap;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int n_cand = L - n_stab;
+  const int kk = n_keep - n_stab;      // candidates to keep, 0 <= kk <= n_cand
+
+  if (IN_LDS)
+    for (int i = tid; i < n_cand; i += SEL_THREADS) keys[i] = score_key(s[i]);
+  auto key_at = [&](int i) -> uint32_t { return IN_LDS ? keys[i] : score_key(s[i]); };
+
+  uint32_t tau, need_eq;
+  if (kk >= n_cand) {          // everything fits
+    tau = 0u; need_eq = 0xffffffffu;
+    __syncthreads();
+  } else if (kk == 0) {        // stabilizers fill the budget
+    tau = 0xffffffffu; need_eq = 0u;
+    __syncthreads();
+  } else {
+    uint32_t prefix = 0u, mask = 0u, remaining = (uint32_t)kk;
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      if (tid < 256) hist[tid] = 0u;
+      __syncthreads();
+      for (int i = tid; i < n_cand; i += SEL_THREADS) {
+        uint32_t key = key_at(i);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        // lane l owns bins 255-4l .. 252-4l; scan from the largest digit down
+        const int b0 = 255 - 4 * lane;
+        uint32_t c0 = hist[b0], c1 = hist[b0 - 1], c2 = hist[b0 - 2], c3 = hist[b0 - 3];
+        uint32_t sum4 = c0 + c1 + c2 + c3;
+        uint32_t incl = sum4;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          uint32_t y = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += y;
+        }
+        uint32_t excl = incl - sum4;
+        if (excl < remaining && remaining <= incl) {
+          uint32_t r = remaining - excl;
+          uint32_t dgt, above;
+          if (r <= c0) { dgt = b0; above = excl; }
+          else if (r <= c0 + c1) { dgt = b0 - 1; above = excl + c0; }
+          else if (r <= c0 + c1 + c2) { dgt = b0 - 2; above = excl + c0 + c1; }
+          else { dgt = b0 - 3; above = excl + c0 + c1 + c2; }
+          bc[0] = prefix | (dgt << shift);
+          bc[1] = remaining - above;
+        }
+      }
+      __syncthreads();
+      prefix = bc[0];
+      remaining = bc[1];
+      mask |= 0xffu << shift;
+    }
+    tau = prefix;
+    need_eq = remaining;
+  }
+
+  // ---- ordered compaction: each wave owns a contiguous range, rounds of 64 consecutive slots ----
+  const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
+  const int w_lo = wave * wseg;
+  const int w_hi = min(n_cand, w_lo + wseg);
+  uint32_t tot_gt = 0, tot_eq = 0;
+  for (int base = w_lo; base < w_hi; base += 64) {
+    int i = base + lane;
+    uint32_t key = (i < w_hi) ? key_at(i) : 0u;
+    bool gt = (i < w_hi) && key > tau;
+    bool eq = (i < w_hi) && key == tau;
+    tot_gt += __popcll(__ballot(gt));
+    tot_eq += __popcll(__ballot(eq));
+  }
+  if (lane == 0) { wsum[wave] = tot_gt; wsum[SEL_WAVES + wave] = tot_eq; }
+  __syncthreads();
+  uint32_t run_gt = 0, run_eq = 0;
+  for (int w = 0; w < wave; ++w) { run_gt += wsum[w]; run_eq += wsum[SEL_WAVES + w]; }
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int32_t* out = kept + (int64_t)m * kept_stride;
+  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 : nullptr;
+  for (int base = w_lo; base < w_hi; base += 64) {
+    int i = base + lane;
+    uint32_t key = (i < w_hi) ? key_at(i) : 0u;
+    bool gt = (i < w_hi) && key > tau;
+    bool eq = (i < w_hi) && key == tau;
+    uint64_t bg = __ballot(gt), be = __ballot(eq);
+    uint32_t gt_before = run_gt + __popcll(bg & lt_mask);
+    uint32_t eq_before = run_eq + __popcll(be & lt_mask);
+    bool keep = gt || (eq && eq_before < need_eq);
+    if (keep) {
+      uint32_t pos = gt_before + min(eq_before, need_eq);
+      out[pos] = i;
+      if (out2) out2[pos] = i;
+    }
+    run_gt += __popcll(bg);
+    run_eq += __popcll(be);
+  }
+  for (int i = n_cand + tid; i < L; i += SEL_THREADS) {
+    out[kk + (i - n_cand)] = i;
+    if (out2) out2[kk + (i - n_cand)] = i;
+  }
+}
+
+static int g_lds_limit = -1;   // bytes of dynamic LDS the in-LDS variant may use
+
+void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int32_t* kept,
+                   int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
+  if (g_lds_limit < 0) {
+    g_lds_limit = 64 * 1024;
+    if (hipFuncSetAttribute((const void*)select_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024) == hipSuccess)
+      g_lds_limit = 160 * 1024;
+    else
+      (void)hipGetLastError();
+  }
+  const int n_cand = L - n_stab;
+  size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);
+  if (need <= (size_t)g_lds_limit)
+    hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, S, cap, L, n_keep, n_stab,
+                       kept, kept_stride, kept2, stride2);
+  else
+    hipLaunchKernelGGL(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, S,
+                       cap, L, n_keep, n_stab, kept, kept_stride, kept2, stride2);
+}
+
+}  // namespace locret

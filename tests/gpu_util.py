@@ -1,0 +1,69 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, drive the library and the
+oracle side by side, compare under the stated tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.locret_oracle import LocretLayerOracle
+from paper_2410_01805_amd import synth
+
+DEV = "cuda:0"
+
+
+def tdtype(w):
+    return torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+
+def dev(x32: np.ndarray, w) -> torch.Tensor:
+    """float32 array holding storage-representable values -> device tensor of the storage type."""
+    return torch.from_numpy(np.ascontiguousarray(x32)).to(DEV).to(tdtype(w)).contiguous()
+
+
+def make_layer(w):
+    from paper_2410_01805_amd import binding as B
+    layer = B.LocretLayer(B.config_from_workload(w), DEV)
+    W1, W2 = synth.weights(w)
+    layer.set_weights(dev(W1, w), dev(W2, w))
+    return layer, W1, W2
+
+
+def make_oracle(w, W1, W2):
+    return LocretLayerOracle(w.h, w.h_kv, w.d, w.b, W1, W2, w.rh_kv_expand, w.rope, w.theta)
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy() if t.dtype in (torch.bfloat16, torch.float32) else t.cpu().numpy()
+
+
+# Tolerances.  float32 path: every product and sum is float32 against the oracle's float64, error
+# grows like sqrt(terms) * 2^-24, far inside 1e-5 * max(1, |ref|).  bf16 path: inputs are identical
+# (already bf16), the kernel rounds rotated q/k and the probabilities to bf16 (2^-9 relative each)
+# and the output to bf16; 2e-2 of the tensor's scale bounds that with margin.
+def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite values from the GPU"
+    diff = np.abs(got - ref)
+    if dtype == "f32":
+        bound = 1e-5 * np.maximum(1.0, np.abs(ref))
+        bad = diff > bound
+        assert not bad.any(), f"{what}: max |d|={diff.max():.3e} (f32 bar 1e-5), {bad.sum()} of {bad.size} off"
+    else:
+        scale = np.abs(ref).max()
+        rms = np.sqrt(np.mean(ref ** 2))
+        assert diff.max() <= 2e-2 * scale, f"{what}: max |d|={diff.max():.3e} vs 2e-2*{scale:.3e}"
+        bad = diff > 2e-2 * np.abs(ref) + 2e-2 * rms
+        assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} elements outside 2e-2 rel + 2e-2 rms"
+
+
+def near_threshold_ok(scores_cat: np.ndarray, kept_gpu, kept_ref, tol_rel: float) -> bool:
+    """Free-running protocol: units in the symmetric difference must sit within tol of the
+    selection threshold (the smallest kept candidate score)."""
+    a, b = set(kept_gpu.tolist()), set(kept_ref.tolist())
+    sym = sorted(a ^ b)
+    if not sym:
+        return True
+    thr = min(scores_cat[i] for i in (a & b)) if (a & b) else 0.0
+    lim = tol_rel * max(1e-30, float(np.abs(scores_cat).max()))
+    return all(abs(float(scores_cat[i]) - thr) <= lim for i in sym)

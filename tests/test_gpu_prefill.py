@@ -1,0 +1,172 @@
+"""GPU parity: the whole chunk step (locret_prefill_chunk) and the retaining head (locret_score)
+against the oracle on the same seeded inputs.
+
+Teacher-forced runs feed the oracle's float32 scores to the selection, so kept indices must be
+bit-exact and the caches identical for the whole stream; attention and the library's own scores
+are compared under the tolerance.  Free-running runs let the library select on its own scores;
+any unit the two sides disagree on must lie within the score tolerance of the threshold."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_01805_amd import synth
+from tests.gpu_util import DEV, assert_close, dev, host, make_layer, make_oracle, near_threshold_ok
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_stream(w, teacher_forced=True, chunk_sizes=None, last_chunk_unmasked=False, attn_rows=None):
+    layer, W1, W2 = make_layer(w)
+    o = make_oracle(w, W1, W2)
+    lo = 0
+    sizes = chunk_sizes or [w.B] * w.n_chunks
+    diverged = False
+    for step, T in enumerate(sizes):
+        hi = min(w.N, lo + T)
+        if hi <= lo:
+            break
+        q, k, v = synth.tokens(w, lo, hi)
+        n_stab = 0 if (last_chunk_unmasked and hi == w.N) else w.n_s
+        n_c = o.n_c
+        scat_before = [np.concatenate([o.S[m], np.zeros(hi - lo, np.float32)]) for m in range(w.h_kv)]
+        out_ref, sc_ref, kept_ref = o.prefill_chunk(q, k, v, n_stab, attn_rows=attn_rows)
+        sin = torch.from_numpy(sc_ref).to(DEV) if teacher_forced else None
+        out, sc, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), n_stab, scores_in=sin)
+        tag = f"{w.name} chunk {step}"
+        sc = sc.cpu().numpy()
+        assert_close(sc, sc_ref, w.dtype, tag + " scores")
+        if not diverged:
+            g, r = host(out), out_ref
+            if attn_rows is not None:
+                g, r = g[attn_rows], r[attn_rows]
+            assert_close(g, r, w.dtype, tag + " attention")
+        n_keep = min(n_c + (hi - lo), w.b)
+        got = kept.cpu().numpy()[:, :n_keep]
+        if teacher_forced:
+            np.testing.assert_array_equal(got, kept_ref, err_msg=tag)
+        else:
+            for m in range(w.h_kv):
+                scat = scat_before[m]
+                scat[n_c:] = sc_ref[m]
+                if not np.array_equal(got[m], kept_ref[m]):
+                    diverged = True
+                    tol = 1e-5 if w.dtype == "f32" else 2e-2
+                    assert near_threshold_ok(scat, got[m], kept_ref[m], tol), tag
+            if diverged:
+                break
+        lo = hi
+    return layer, o, diverged
+
+
+SMALL = [
+    dict(name="f32_gqa", dtype="f32", h=8, h_kv=2, d=64, N=1500, B=200, b=400, n_s=32, d_R=64, rope=False),
+    dict(name="f32_gqa_expand", dtype="f32", h=8, h_kv=2, d=64, N=900, B=200, b=400, n_s=32, d_R=128, rope=False,
+         rh_kv_expand=1),
+    dict(name="f32_rope", dtype="f32", h=4, h_kv=2, d=32, N=1200, B=160, b=300, n_s=40, d_R=64, rope=True),
+    dict(name="f32_mha_d16", dtype="f32", h=3, h_kv=3, d=16, N=700, B=100, b=150, n_s=0, d_R=40, rope=True),
+    dict(name="bf16_llama_like", dtype="bf16", h=8, h_kv=2, d=128, N=2500, B=300, b=700, n_s=100, d_R=128,
+         theta=500000.0),
+    dict(name="bf16_phi_like", dtype="bf16", h=4, h_kv=4, d=96, N=2000, B=256, b=600, n_s=64, d_R=128),
+    dict(name="bf16_d64_norope", dtype="bf16", h=4, h_kv=1, d=64, N=1500, B=250, b=500, n_s=500, d_R=256,
+         rope=False),
+    dict(name="bf16_ns_gt_B", dtype="bf16", h=4, h_kv=2, d=128, N=1800, B=128, b=640, n_s=300, d_R=128),
+]
+
+
+@pytest.mark.parametrize("kw", SMALL, ids=[c["name"] for c in SMALL])
+def test_teacher_forced_stream(kw):
+    w = synth.tiny(**kw)
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    K, V, S, P = layer.cache_tensors()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+        np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
+        np.testing.assert_array_equal(S[m].cpu().numpy(), o.S[m])
+    layer.close()
+
+
+def test_ragged_chunks_and_algorithm1_last_chunk():
+    w = synth.tiny(name="ragged", dtype="bf16", h=8, h_kv=2, d=128, N=1500, B=400, b=500, n_s=60, d_R=128)
+    layer, o, _ = _run_stream(w, chunk_sizes=[1, 400, 33, 64, 65, 127, 400, 10, 400], last_chunk_unmasked=True)
+    assert layer.cache_len == o.n_c == 500
+    layer.close()
+
+
+def test_config1_full_stream_teacher_forced():
+    w = synth.WORKLOADS["cfg1_f32_gqa_4k"]
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    assert layer.cache_len == w.b
+    layer.close()
+
+
+def test_config1_full_stream_free_running():
+    w = synth.WORKLOADS["cfg1_f32_gqa_4k"]
+    layer, o, diverged = _run_stream(w, teacher_forced=False)
+    layer.close()
+
+
+def test_free_running_bf16():
+    w = synth.tiny(name="free_bf16", dtype="bf16", h=8, h_kv=2, d=128, N=3000, B=512, b=1024, n_s=64, d_R=256)
+    layer, o, _ = _run_stream(w, teacher_forced=False)
+    layer.close()
+
+
+def test_score_entry_point_matches_and_leaves_cache_alone():
+    for kw in (SMALL[0], SMALL[4]):
+        w = synth.tiny(**kw)
+        layer, W1, W2 = make_layer(w)
+        o = make_oracle(w, W1, W2)
+        q, k, v = synth.tokens(w, 0, w.B - 3)
+        sc = layer.score(dev(q, w), dev(k, w), dev(v, w)).cpu().numpy()
+        assert_close(sc, o.score(q, k, v), w.dtype, w.name + " locret_score")
+        assert layer.cache_len == 0
+        layer.close()
+
+
+def test_tail_pass_without_eviction_then_capacity_error():
+    from paper_2410_01805_amd import binding as B
+    w = synth.tiny(name="tail", dtype="f32", h=4, h_kv=2, d=32, N=600, B=100, b=250, n_s=20, d_R=64, rope=True)
+    layer, W1, W2 = make_layer(w)
+    o = make_oracle(w, W1, W2)
+    for c in range(5):
+        q, k, v = synth.chunk(w, c)
+        layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), w.n_s)
+        o.prefill_chunk(q, k, v, w.n_s)
+    # the n_loc pass of Algorithm 1: attend and append, no eviction
+    q, k, v = synth.tokens(w, 500, 560)
+    out, sc, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), 0, evict=False)
+    out_ref, sc_ref, _ = o.prefill_chunk(q, k, v, 0, evict=False)
+    assert kept is None and layer.cache_len == o.n_c == 310
+    assert_close(host(out), out_ref, "f32", "tail attention")
+    K, V, S, P = layer.cache_tensors()
+    np.testing.assert_array_equal(P[0].cpu().numpy(), o.P[0])
+    # 310 + 100 > budget + chunk_max = 350
+    q, k, v = synth.tokens(w, 0, 100)
+    with pytest.raises(B.LocretError) as e:
+        layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), 0, evict=False)
+    assert e.value.code == B.LOCRET_ESTATE
+    layer.close()
+
+
+def test_state_and_argument_errors_on_device():
+    from paper_2410_01805_amd import binding as B
+    w = synth.tiny(name="err", dtype="f32", h=4, h_kv=2, d=32, N=600, B=100, b=250, n_s=20, d_R=64)
+    layer = B.LocretLayer(B.config_from_workload(w), DEV)
+    q, k, v = (dev(x, w) for x in synth.tokens(w, 0, 100))
+    with pytest.raises(B.LocretError) as e:       # weights not set
+        layer.prefill_chunk(q, k, v, 0)
+    assert e.value.code == B.LOCRET_ESTATE
+    W1, W2 = synth.weights(w)
+    layer.set_weights(dev(W1, w), dev(W2, w))
+    with pytest.raises(B.LocretError) as e:       # stabilizers beyond the budget
+        layer.prefill_chunk(q, k, v, 251)
+    assert e.value.code == B.LOCRET_EINVAL
+    q2, k2, v2 = (dev(x, w) for x in synth.tokens(w, 0, 101))
+    with pytest.raises(B.LocretError) as e:       # T beyond chunk_max
+        layer.prefill_chunk(q2, k2, v2, 0)
+    assert e.value.code == B.LOCRET_ESHAPE
+    with pytest.raises(B.LocretError) as e:       # misaligned pointer
+        B.locret_score(layer.ctx, q.data_ptr() + 4, k, v, 50, torch.empty(2, 50, device=DEV))
+    assert e.value.code == B.LOCRET_EALIGN
+    assert layer.cache_len == 0                   # nothing was changed by the failed calls
+    layer.close()
