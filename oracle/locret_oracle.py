@@ -177,7 +177,7 @@ class LocretLayerOracle:
     # -- step 2 -------------------------------------------------------------------------------
     def score(self, q, k, v) -> np.ndarray:
         """float32 [h_kv][T] (the storage precision of scores)."""
-        return retaining_head(q, k, v, self.W1, self.W2, self.rh_kv_expand).T.astype(np.float32)
+        return np.ascontiguousarray(retaining_head(q, k, v, self.W1, self.W2, self.rh_kv_expand).T, dtype=np.float32)
 
     # -- steps 3-5 ----------------------------------------------------------------------------
     def evict_compact(self, scores, k, v, n_stab: int, evict: bool = True) -> np.ndarray:

@@ -9,6 +9,11 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  It must be in the process before
+# liblocret.so is opened so that the dynamic loader binds the library to that same runtime:
+# two runtimes in one process do not share device allocations or streams.
+import torch  # noqa: F401  (memory and streams come from here as well)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "liblocret.so")
 

@@ -1,8 +1,331 @@
-// placeholder until the MFMA kernel lands
+// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950.
+//
+// For each query head j (KV head m = j / g) and query token t of the chunk, keys are the slots
+// [0, n_c + t] of one contiguous K/V array per KV head (retained cache followed by the chunk);
+// softmax is computed online in fp32.
+//
+// Workgroup = 4 wavefronts.  Each wavefront owns QB blocks of 32 queries of one head; the
+// wavefronts of a workgroup share one KV head, so the K/V tiles they stage in LDS are read by
+// every one of them (for g >= 4 the four wavefronts are four query heads of the same group over
+// the same tokens; for g = 1 they are four token ranges of one head).
+//
+// The products are formed transposed, with v_mfma_f32_32x32x16_bf16:
+//   S^T[key][query] = K[key][:] . Q[query][:]      A = K tile rows (LDS), B = Q (registers)
+//   O^T[dim][query] += V^T[dim][key] . P^T[key][query]   A = V^T (LDS), B = P^T (registers)
+// In the 32x32 accumulator layout a lane holds, for ONE query (column lane%32), 16 keys of a
+// 32-key block: keys (r/4)*8 + (lane/32)*4 + r%4 for register r.  Hence the running max, the
+// rescale factor and the row sum are per-lane scalars, the only cross-lane step being one
+// exchange with lane^32, and P^T leaves the accumulator already in B-operand order provided the
+// V^T tile stores its keys in the matching order (each group of 16 keys as 0-3, 8-11, 4-7, 12-15).
+//
+// K tile in LDS: [64 keys][D + 8] (16-byte pad: conflict-free 16-byte row reads).
+// V^T tile in LDS: [D][64 keys], transposed on the way in by 4x8 register blocks, 16-byte chunks
+// XOR-swizzled by (row ^ row>>3) & 7 so that both the transposing writes and the row reads spread
+// over the banks.  Tiles are double buffered through registers: one barrier per 64 keys.
+#include "device_util.h"
 #include "kernels.h"
+
 namespace locret {
-void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                           float scale, hipStream_t st) {
-  launch_attention_simple(D, q, Kx, V, out, T, n_c, scale, st);
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int KT = 64;   // keys per tile
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 x = {a, b};
+  bf16x2 y = __builtin_convertvector(x, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
+  return *(uint32_t*)&y;
 }
+
+template <int D>
+struct AttnSmem {
+  static constexpr int KSTR = D + 8;                 // bf16 elements per K row
+  bf16_t K[2][KT * KSTR];
+  bf16_t Vt[2][D * KT];
+};
+
+// position (in bf16 elements) of key-quad kq (4 keys) of row `row` inside a V^T tile
+__device__ __forceinline__ int vt_quad_off(int row, int kq) {
+  int qg = kq & 3;
+  int kqp = (kq & ~3) | ((qg == 1) ? 2 : (qg == 2) ? 1 : qg);   // 0-3, 8-11, 4-7, 12-15 inside each 16
+  int chunk = (kqp >> 1) ^ ((row ^ (row >> 3)) & 7);
+  return row * KT + chunk * 8 + (kqp & 1) * 4;
+}
+
+template <int D, int QB>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
+                                                        const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
+                                                        int Tn, int h, int g, int cap, int n_c, float c_log2,
+                                                        int hpw, int n_hgroups, int n_ttiles) {
+  constexpr int NKS = D / 16;          // k-steps over the head dim for S
+  constexpr int NDB = D / 32;          // 32-row blocks of O^T
+  constexpr int KCH = D / 8;           // 16-byte chunks per K row
+  constexpr int K_LD = (KT * KCH) / 256;   // K chunks per thread per tile
+  constexpr int V_BLK = (KT / 4) * KCH;    // 4-key x 8-dim blocks per V tile
+  constexpr int KSTR = AttnSmem<D>::KSTR;
+  __shared__ AttnSmem<D> sm;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int n32 = lane & 31;
+  const int hi = lane >> 5;
+
+  // ---- workgroup -> (head group, token tile); consecutive ids go to different XCDs, so the
+  // ---- head group is taken from id % 8 to keep one KV head's K/V in one XCD's L2 --------------
+  const int bid = blockIdx.x;
+  int hgroup, tt;
+  if ((n_hgroups & 7) == 0) {
+    const int g8 = n_hgroups >> 3;
+    hgroup = (bid & 7) * g8 + (bid >> 3) % g8;
+    tt = bid / n_hgroups;
+  } else {
+    hgroup = bid % n_hgroups;
+    tt = bid / n_hgroups;
+  }
+  tt = n_ttiles - 1 - tt;                      // longest key ranges first
+  const int wph = 4 / hpw;                     // wavefronts per head
+  const int TW = wph * 32 * QB;                // tokens per workgroup
+  const int t0 = tt * TW;
+  const int j = hgroup * hpw + wave / wph;     // query head of this wavefront
+  const int m = j / g;
+  const int tw0 = t0 + (wave % wph) * 32 * QB; // first token of this wavefront
+  const int t_last_wg = min(Tn, t0 + TW) - 1;
+  const int n_keys = n_c + t_last_wg + 1;      // slots the workgroup stages
+  const int n_tiles = (n_keys + KT - 1) / KT;
+  const int wave_last_slot = n_c + min(Tn - 1, tw0 + 32 * QB - 1);   // < 0 never: tw0 may exceed Tn
+
+  const bf16_t* Kb = Kx + (int64_t)m * cap * D;
+  const bf16_t* Vb = V + (int64_t)m * cap * D;
+
+  // ---- Q fragments: B operand, lane = query n32 of block qb, dims ks*16 + hi*8 .. +8 ------------
+  bf16x8 qf[QB][NKS];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    int t = min(tw0 + qb * 32 + n32, Tn - 1);
+    const bf16_t* qp = q + ((int64_t)t * h + j) * D + hi * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + ks * 16);
+  }
+
+  f32x16 oacc[NDB][QB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+
+  // ---- staging registers -------------------------------------------------------------------
+  uint4 kreg[K_LD];
+  uint4 vreg[4];
+  const int vblk = tid;                        // one 4-key x 8-dim block per thread (if < V_BLK)
+  const int v_kq = vblk & 15;                  // key quad: fastest over lanes -> LDS-friendly writes
+  const int v_d8 = vblk >> 4;                  // 8-dim column group
+
+  auto load_tile = [&](int tile) {
+    const int base = tile * KT;
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i) {
+      int c = tid + 256 * i;
+      int row = c / KCH, col = c % KCH;
+      int slot = base + row;
+      kreg[i] = (slot < n_keys) ? *(const uint4*)(Kb + (int64_t)slot * D + col * 8) : make_uint4(0, 0, 0, 0);
+    }
+    if (vblk < V_BLK) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int slot = base + v_kq * 4 + i;
+        vreg[i] = (slot < n_keys) ? *(const uint4*)(Vb + (int64_t)slot * D + v_d8 * 8) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < K_LD; ++i) {
+      int c = tid + 256 * i;
+      int row = c / KCH, col = c % KCH;
+      *(uint4*)(&sm.K[buf][row * KSTR + col * 8]) = kreg[i];
+    }
+    if (vblk < V_BLK) {
+      const uint32_t* r0 = (const uint32_t*)&vreg[0];
+      const uint32_t* r1 = (const uint32_t*)&vreg[1];
+      const uint32_t* r2 = (const uint32_t*)&vreg[2];
+      const uint32_t* r3 = (const uint32_t*)&vreg[3];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {            // word p holds dims 2p (low half) and 2p+1 (high half)
+        uint2 even, odd;
+        even.x = (r0[p] & 0xffffu) | (r1[p] << 16);
+        even.y = (r2[p] & 0xffffu) | (r3[p] << 16);
+        odd.x = (r0[p] >> 16) | (r1[p] & 0xffff0000u);
+        odd.y = (r2[p] >> 16) | (r3[p] & 0xffff0000u);
+        int row = v_d8 * 8 + 2 * p;
+        *(uint2*)(&sm.Vt[buf][vt_quad_off(row, v_kq)]) = even;
+        *(uint2*)(&sm.Vt[buf][vt_quad_off(row + 1, v_kq)]) = odd;
+      }
+    }
+  };
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int buf = tile & 1;
+    const int base = tile * KT;
+    if (tile + 1 < n_tiles) load_tile(tile + 1);
+
+    if (base <= wave_last_slot) {              // wave-uniform: later tiles hold nothing this wave sees
+      // ---- S^T = K Q^T ----------------------------------------------------------------------
+      f32x16 sacc[2][QB];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16_t* kp = &sm.K[buf][(kb * 32 + n32) * KSTR + hi * 8];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          bf16x8 a = *(const bf16x8*)(kp + ks * 16);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+        }
+      }
+      // ---- online softmax, per query block ------------------------------------------------------
+      uint4 pb[QB][4];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int limit = n_c + min(tw0 + qb * 32 + n32, Tn - 1);     // last visible slot of this lane's query
+        const bool need_mask = base + KT - 1 > n_c + tw0 + qb * 32;   // wave-uniform
+        if (need_mask) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              int slot = base + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
+              if (slot > limit) sacc[kb][qb][r] = -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[qb], mx);          // finite from tile 0 on (slot 0 is visible to all)
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c_log2);
+        const float mc = m_new * c_log2;
+        m_run[qb] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][r], c_log2, -mc));
+            psum += p[r];
+          }
+          pb[qb][kb * 2 + 0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
+                                          pack_bf16(p[6], p[7]));
+          pb[qb][kb * 2 + 1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
+                                          pack_bf16(p[14], p[15]));
+        }
+        l_run[qb] = l_run[qb] * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
+      }
+      // ---- O^T += V^T P^T -----------------------------------------------------------------------
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const int row = db * 32 + n32;
+        const int swz = (row ^ (row >> 3)) & 7;
+        const bf16_t* vp = &sm.Vt[buf][row * KT];
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+          bf16x8 a = *(const bf16x8*)(vp + (((kc * 2 + hi) ^ swz) * 8));
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, *(const bf16x8*)&pb[qb][kc], oacc[db][qb], 0, 0, 0);
+        }
+      }
+    }
+
+    if (tile + 1 < n_tiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: O = O^T / l, lane holds 4 consecutive dims per (db, r/4) for its query -------------
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int t = tw0 + qb * 32 + n32;
+    float l = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+    if (t < Tn) {
+      const float inv = 1.f / l;
+      bf16_t* op = out + ((int64_t)t * h + j) * D;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          uint2 w;
+          w.x = pack_bf16(oacc[db][qb][rq * 4 + 0] * inv, oacc[db][qb][rq * 4 + 1] * inv);
+          w.y = pack_bf16(oacc[db][qb][rq * 4 + 2] * inv, oacc[db][qb][rq * 4 + 3] * inv);
+          *(uint2*)(op + db * 32 + rq * 8 + hi * 4) = w;
+        }
+    }
+  }
+}
+
+template <int D, int QB>
+static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
+                        float scale, hipStream_t st) {
+  const int g = Dm.g;
+  const int hpw = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
+  const int wph = 4 / hpw;
+  const int TW = wph * 32 * QB;
+  const int n_hgroups = Dm.h / hpw;
+  const int n_ttiles = (T + TW - 1) / TW;
+  const float c_log2 = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL((attn_mfma_kernel<D, QB>), dim3(n_hgroups * n_ttiles), dim3(256), 0, st, (const bf16_t*)q,
+                     (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
+                     n_hgroups, n_ttiles);
+}
+
+static int attn_qb() {
+  static int qb = -1;
+  if (qb < 0) {
+    const char* e = getenv("LOCRET_ATTN_QB");
+    qb = (e && e[0] == '1') ? 1 : 2;
+  }
+  return qb;
+}
+
+void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
+                           float scale, hipStream_t st) {
+  const int qb = attn_qb();
+#define LOCRET_CASE(DD)                                                          \
+  case DD:                                                                       \
+    if (qb == 1) attn_launch<DD, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);       \
+    else attn_launch<DD, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);               \
+    break;
+  switch (Dm.d) {
+    LOCRET_CASE(64)
+    LOCRET_CASE(96)
+    LOCRET_CASE(128)
+    default: launch_attention_simple(Dm, q, Kx, V, out, T, n_c, scale, st);
+  }
+#undef LOCRET_CASE
+}
+
 }  // namespace locret

@@ -232,8 +232,8 @@ __global__ void score_reduce_kernel(const float* __restrict__ part, int n_parts,
   int gid = blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= h_kv * Tn) return;
   int m = gid / Tn, t = gid % Tn;
-  float sum = 0.f;
-  for (int p = 0; p < n_parts; ++p) sum += part[((int64_t)p * h_kv + m) * part_T + t];
+  float sum = part[(int64_t)m * part_T + t];   // a single part is copied bit for bit (-0 stays -0)
+  for (int p = 1; p < n_parts; ++p) sum += part[((int64_t)p * h_kv + m) * part_T + t];
   if (S) S[(int64_t)m * cap + n_c + t] = sum;
   if (out) out[(int64_t)m * Tn + t] = sum;
 }

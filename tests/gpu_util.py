@@ -38,23 +38,28 @@ def host(t: torch.Tensor) -> np.ndarray:
 
 # Tolerances.  float32 path: every product and sum is float32 against the oracle's float64, error
 # grows like sqrt(terms) * 2^-24, far inside 1e-5 * max(1, |ref|).  bf16 path: inputs are identical
-# (already bf16), the kernel rounds rotated q/k and the probabilities to bf16 (2^-9 relative each)
-# and the output to bf16; 2e-2 of the tensor's scale bounds that with margin.
-def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = ""):
+# (already bf16); the kernel rounds rotated q/k and the probabilities to bf16 (2^-9 relative each)
+# and the output to bf16.  "2e-2 relative" is taken against the scale of the vector an element
+# belongs to: an attention output row is one convex combination of value rows, so its error
+# scales with that row's magnitude (rows that see few keys are O(1), rows that average thousands
+# are O(0.01)); scores are compared against the scale of the whole tensor.
+def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", per_row: bool = False):
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
     assert np.isfinite(got).all(), f"{what}: non-finite values from the GPU"
     diff = np.abs(got - ref)
     if dtype == "f32":
         bound = 1e-5 * np.maximum(1.0, np.abs(ref))
-        bad = diff > bound
-        assert not bad.any(), f"{what}: max |d|={diff.max():.3e} (f32 bar 1e-5), {bad.sum()} of {bad.size} off"
     else:
         scale = np.abs(ref).max()
-        rms = np.sqrt(np.mean(ref ** 2))
         assert diff.max() <= 2e-2 * scale, f"{what}: max |d|={diff.max():.3e} vs 2e-2*{scale:.3e}"
-        bad = diff > 2e-2 * np.abs(ref) + 2e-2 * rms
-        assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} elements outside 2e-2 rel + 2e-2 rms"
+        rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True)) if per_row else np.sqrt(np.mean(ref ** 2))
+        bound = 2e-2 * np.abs(ref) + 2e-2 * rms
+    bad = diff > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(diff - bound), diff.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance ({dtype}); worst at {i}: "
+                             f"got {got[i]:.6g} ref {ref[i]:.6g} bound {np.broadcast_to(bound, diff.shape)[i]:.3g}")
 
 
 def near_threshold_ok(scores_cat: np.ndarray, kept_gpu, kept_ref, tol_rel: float) -> bool:

@@ -39,7 +39,7 @@ def _run_stream(w, teacher_forced=True, chunk_sizes=None, last_chunk_unmasked=Fa
             g, r = host(out), out_ref
             if attn_rows is not None:
                 g, r = g[attn_rows], r[attn_rows]
-            assert_close(g, r, w.dtype, tag + " attention")
+            assert_close(g, r, w.dtype, tag + " attention", per_row=True)
         n_keep = min(n_c + (hi - lo), w.b)
         got = kept.cpu().numpy()[:, :n_keep]
         if teacher_forced:
@@ -137,7 +137,7 @@ def test_tail_pass_without_eviction_then_capacity_error():
     out, sc, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), 0, evict=False)
     out_ref, sc_ref, _ = o.prefill_chunk(q, k, v, 0, evict=False)
     assert kept is None and layer.cache_len == o.n_c == 310
-    assert_close(host(out), out_ref, "f32", "tail attention")
+    assert_close(host(out), out_ref, "f32", "tail attention", per_row=True)
     K, V, S, P = layer.cache_tensors()
     np.testing.assert_array_equal(P[0].cpu().numpy(), o.P[0])
     # 310 + 100 > budget + chunk_max = 350
