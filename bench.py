@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the Locret chunk step on one MI355X.
+
+A step is one locret_prefill_chunk call (attention + retaining head + select + compact) on one
+chunk of the synthetic 128K-token stream; the timed region is K consecutive chunks starting from
+an empty cache (K = all 32 chunks by default, so `value` is whole-stream prefill tokens/s per
+layer at 131072 tokens).  Inputs are generated on the host from the seeded recipe and are resident
+in HBM before the clock starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+PEAK_F32_TFLOPS = 157.3
+
+
+def attention_flops(w, n_c, T):
+    """QK^T + PV over the keys each query really sees (cache + causal part of the chunk)."""
+    return 4.0 * w.h * w.d * (T * n_c + T * (T + 1) / 2.0)
+
+
+def score_flops(w, T):
+    K = (w.h + 2 * w.h_kv) * w.d
+    return 2.0 * T * K * w.d_R + 2.0 * T * w.d_R * w.h_kv
+
+
+def evict_bytes(w, n_c, T):
+    """scores in; kept scores + positions out; K and V rows read and written once; rotated-K shadow written."""
+    s = 2 if w.dtype == "bf16" else 4
+    L = n_c + T
+    n_keep = min(L, w.b)
+    moved = n_keep if L > w.b else 0
+    return w.h_kv * (L * 4 + n_keep * 8 * (1 if moved else 0) + 4 * moved * w.d * s + (moved * w.d * s if w.rope else 0))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="cfg3_llama_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=48, help="query rows per head in the oracle's attention sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus above 1 is not supported (no collectives are built)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2410_01805_amd import binding as B
+    from paper_2410_01805_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    n_chunks = w.n_chunks
+    K = args.steps if args.steps is not None else n_chunks
+    W = args.warmup
+    dev = torch.device("cuda:0")
+    td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    # ---- inputs: generated per chunk on host threads, uploaded, resident before timing ------------------
+    need = min(n_chunks, max(K, W))
+    t_gen = time.time()
+    with ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0)))) as ex:
+        host_chunks = list(ex.map(lambda c: synth.chunk(w, c), range(need)))
+    chunks = [tuple(torch.from_numpy(x).to(dev).to(td).contiguous() for x in hc) for hc in host_chunks]
+    W1h, W2h = synth.weights(w)
+    layer = B.LocretLayer(B.config_from_workload(w), dev)
+    layer.set_weights(torch.from_numpy(W1h).to(dev).to(td), torch.from_numpy(W2h).to(dev).to(td))
+    out = torch.empty((w.B, w.h, w.d), dtype=td, device=dev)
+    scores = torch.empty((w.h_kv, w.B), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    def step(i):
+        c = i % need
+        if c == 0:
+            B.locret_reset(layer.ctx)
+        q, k, v = chunks[c]
+        T = q.shape[0]
+        B.locret_prefill_chunk(layer.ctx, q, k, v, T, w.n_s, 1, None, out, scores, None)
+        return T
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region ---------------------------------------------------------------------------------
+    B.locret_reset(layer.ctx)
+    B.locret_profile_enable(layer.ctx, K)
+    plan = []           # (n_c before the call, T) per timed step, for the work model
+    n_c = 0
+    for i in range(K):
+        c = i % need
+        if c == 0:
+            n_c = 0
+        T = chunks[c][0].shape[0]
+        plan.append((n_c, T))
+        n_c = min(n_c + T, w.b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    tokens = 0
+    for i in range(K):
+        tokens += step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    total_ms = e0.elapsed_time(e1)
+    stage_ms, n_prof = B.locret_profile_read(layer.ctx)
+    B.locret_profile_enable(layer.ctx, 0)
+
+    fl_attn = sum(attention_flops(w, nc, T) for nc, T in plan)
+    fl_score = sum(score_flops(w, T) for nc, T in plan)
+    by_evict = sum(evict_bytes(w, nc, T) for nc, T in plan)
+    ms = dict(zip(B.PROF_STAGE_NAMES, stage_ms))
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    attn_tflops = fl_attn / (ms["attention"] * 1e-3) / 1e12
+    roofline = {
+        "kernel": "attention", "bound": "mfma", "achieved": round(attn_tflops, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(attn_tflops / peak, 4), "traffic": None,
+        "avg_launch_ms": round(ms["attention"] / max(1, n_prof), 4),
+        "flops_per_launch_steady": attention_flops(w, w.b, w.B),
+    }
+    mlp_tflops = fl_score / (ms["retaining_head"] * 1e-3) / 1e12
+    evict_ms = ms["select"] + ms["compact"]
+    evict_gbs = by_evict / (evict_ms * 1e-3) / 1e9 if evict_ms > 0 else 0.0
+    extra = {
+        "stage_ms_per_step": {k: round(v / max(1, n_prof), 4) for k, v in ms.items()},
+        "retaining_head": {"achieved": round(mlp_tflops, 2), "unit": "TFLOP/s", "frac": round(mlp_tflops / peak, 4)},
+        "attention_plus_retaining_head_frac": round((fl_attn + fl_score) / ((ms["attention"] + ms["retaining_head"]) * 1e-3) / 1e12 / peak, 4),
+        "select_compact": {"bound": "hbm", "achieved": round(evict_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": round(evict_gbs / PEAK_HBM_GBS, 4)},
+        "input_gen_s": round(t_gen, 1),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, host_chunks, args.cpu_rows)
+
+    line = {
+        "metric": "prefill tokens/sec per layer at 128K ctx", "value": round(tokens / (total_ms * 1e-3), 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(total_ms / K, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "tokens": w.N, "chunk": w.B, "budget": w.b, "stabilizers": w.n_s,
+                   "heads": f"{w.h}q/{w.h_kv}kv x{w.d}", "d_R": w.d_R},
+        "roofline": roofline, "cpu_baseline": cpu, **extra,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(w, host_chunks, rows_per_head):
+    """The oracle, as it stands, on one steady-state chunk of the same workload: retaining head,
+    selection and compaction in full; attention on a sample of query rows (rows are independent),
+    extrapolated linearly to the whole chunk from two sample sizes."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle.locret_oracle import LocretLayerOracle
+    from paper_2410_01805_amd import synth
+
+    W1, W2 = synth.weights(w)
+    o = LocretLayerOracle(w.h, w.h_kv, w.d, w.b, W1, W2, w.rh_kv_expand, w.rope, w.theta)
+    # fill the cache to the budget with the first chunks (scores come from the oracle itself; untimed)
+    c = 0
+    while o.n_c < w.b and c < len(host_chunks) - 1:
+        q, k, v = host_chunks[c]
+        o.prefill_chunk(q, k, v, w.n_s, want_attn=False)
+        c += 1
+    q, k, v = host_chunks[c]
+    T = q.shape[0]
+    rng = np.random.default_rng(0)
+    r1 = np.sort(rng.choice(T, size=min(T, rows_per_head), replace=False))
+    r2 = np.sort(rng.choice(T, size=min(T, 3 * rows_per_head), replace=False))
+    t0 = time.time(); o.attention(q, k, v, rows=r1); t1 = time.time()
+    o.attention(q, k, v, rows=r2); t2 = time.time()
+    ta, tb = t1 - t0, t2 - t1
+    per_row = max(0.0, (tb - ta) / max(1, len(r2) - len(r1)))
+    fixed = max(0.0, ta - per_row * len(r1))
+    t_attn_full = fixed + per_row * T if len(r1) < T else ta
+    t3 = time.time()
+    sc = o.score(q, k, v)
+    o.evict_compact(sc, k, v, w.n_s)
+    t_rest = time.time() - t3
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {
+        "value": round(T / (t_attn_full + t_rest), 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"one steady-state chunk (n_c={w.b}, T={T}): retaining head + select + compact in full "
+                  f"({t_rest:.2f}s); attention on {len(r1)} and {len(r2)} query rows x {w.h} heads "
+                  f"({ta:.2f}s, {tb:.2f}s), extrapolated linearly to {T} rows ({t_attn_full:.1f}s)",
+    }
+
+
+if __name__ == "__main__":
+    main()

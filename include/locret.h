@@ -59,10 +59,10 @@ typedef struct locret_ctx locret_ctx;   /* opaque host-side handle */
 typedef struct {
   int32_t n_q_heads;      /* h                                                                 */
   int32_t n_kv_heads;     /* h/g; must divide n_q_heads                                        */
-  int32_t head_dim;       /* d: 64, 96 or 128 on the bf16 path; any multiple of 8 up to 128 in f32 */
+  int32_t head_dim;       /* d: 16, 32, 64, 96 or 128 (bf16 with 64/96/128 runs on the matrix cores) */
   int32_t chunk_max;      /* B: largest T of any call                                          */
   int32_t budget;         /* b: cache units kept per KV head                                   */
-  int32_t d_hidden;       /* d_R: retaining-head hidden width (multiple of 128 in bf16, 16 in f32) */
+  int32_t d_hidden;       /* d_R: retaining-head hidden width (bf16: multiples of 128 run on the matrix cores) */
   int32_t rh_kv_expand;   /* 0: W1 has (h + 2 h/g) d rows, the shape Section 3.3 states
                              1: W1 has 3 h d rows; the K and V blocks are repeated g times in
                                 query-head order (query head j reads KV head floor(j/g))      */
@@ -130,6 +130,17 @@ int64_t locret_tokens_seen(const locret_ctx* ctx);
  * evicts.  Any out-pointer may be NULL. */
 int locret_cache_view(const locret_ctx* ctx, const void** K, const void** V, const float** score,
                       const int32_t** orig_pos, int32_t* len, int32_t* row_stride);
+
+/* Per-stage timing for callers that measure (benchmarks, profilers).  locret_profile_enable
+ * creates hipEvents for up to max_calls chunk calls (0 disables and frees them); while enabled,
+ * locret_prefill_chunk records an event at each stage boundary on the call's stream (stages:
+ * 0 append+rotate, 1 attention, 2 retaining head, 3 select, 4 compact).  locret_profile_read waits
+ * for the recorded events, writes the summed milliseconds per stage to stage_ms (HOST, 5 doubles)
+ * and the number of calls covered to *n_calls (HOST), and starts a new window.  Calls beyond
+ * max_calls in one window are not recorded. */
+#define LOCRET_PROF_STAGES 5
+int locret_profile_enable(locret_ctx* ctx, int32_t max_calls);
+int locret_profile_read(locret_ctx* ctx, double* stage_ms, int32_t* n_calls);
 
 void locret_destroy(locret_ctx* ctx);
 

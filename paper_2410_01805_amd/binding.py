@@ -23,8 +23,10 @@ LOCRET_F32, LOCRET_BF16 = 0, 1
 EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
-    "locret_destroy", "locret_strerror",
+    "locret_destroy", "locret_strerror", "locret_profile_enable", "locret_profile_read",
 ]
+LOCRET_PROF_STAGES = 5
+PROF_STAGE_NAMES = ("append", "attention", "retaining_head", "select", "compact")
 
 
 class locret_config(C.Structure):
@@ -62,6 +64,10 @@ def _load() -> C.CDLL:
     lib.locret_cache_view.restype = C.c_int
     lib.locret_cache_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                       C.POINTER(i32), C.POINTER(i32)]
+    lib.locret_profile_enable.restype = C.c_int
+    lib.locret_profile_enable.argtypes = [vp, i32]
+    lib.locret_profile_read.restype = C.c_int
+    lib.locret_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     lib.locret_destroy.restype = None
     lib.locret_destroy.argtypes = [vp]
     lib.locret_strerror.restype = C.c_char_p
@@ -158,6 +164,18 @@ def locret_cache_view(ctx) -> dict:
     _check(lib.locret_cache_view(ctx, C.byref(K), C.byref(V), C.byref(S), C.byref(P), C.byref(n), C.byref(stride)),
            "locret_cache_view")
     return dict(K=K.value, V=V.value, score=S.value, orig_pos=P.value, len=n.value, row_stride=stride.value)
+
+
+def locret_profile_enable(ctx, max_calls: int) -> None:
+    _check(lib.locret_profile_enable(ctx, max_calls), "locret_profile_enable")
+
+
+def locret_profile_read(ctx):
+    """(per-stage milliseconds summed over the recorded calls, number of calls)."""
+    ms = (C.c_double * LOCRET_PROF_STAGES)()
+    n = C.c_int32()
+    _check(lib.locret_profile_read(ctx, ms, C.byref(n)), "locret_profile_read")
+    return list(ms), n.value
 
 
 def locret_destroy(ctx) -> None:

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "../../include/locret.h"
 #include "kernels.h"
@@ -93,6 +94,11 @@ struct locret_ctx {
   int have_weights;
   float scale;
   int mfma_attn, mfma_score;
+  std::vector<hipEvent_t> ev;   // profiling: (LOCRET_PROF_STAGES + 1) events per recorded call
+  int prof_max, prof_calls;
+  void mark(int stage, hipStream_t st) {
+    if (prof_calls < prof_max) (void)hipEventRecord(ev[(size_t)prof_calls * (LOCRET_PROF_STAGES + 1) + stage], st);
+  }
   CacheBuf buf(int i) const {
     CacheBuf b;
     b.K = ws + L.K[i];
@@ -121,9 +127,9 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   if (rc != LOCRET_OK) return rc;
   if (!ws) return LOCRET_EINVAL;
   if (((uintptr_t)ws & (ALIGN - 1)) != 0) return LOCRET_EALIGN;
-  locret_ctx* c = new (std::nothrow) locret_ctx;
+  locret_ctx* c = new (std::nothrow) locret_ctx();
   if (!c) return LOCRET_ENOMEM;
-  memset(c, 0, sizeof(*c));
+  c->cur = 0; c->n_c = 0; c->seen = 0; c->have_weights = 0; c->prof_max = 0; c->prof_calls = 0;
   c->cfg = *cfg;
   fill_dims(cfg, &c->D);
   make_layout(cfg, c->D, &c->L);
@@ -186,6 +192,7 @@ static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, h
   CacheBuf A = c->buf(c->cur);
   int32_t* kept = (int32_t*)(c->ws + c->L.kept);
   launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, kept, b, kept_idx_out, b, st);
+  c->mark(4, st);
   if (L > b) {
     CacheBuf B = c->buf(c->cur ^ 1);
     launch_compact(c->D, A, B, kept, b, n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
@@ -211,17 +218,23 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   void* qr = D.rope ? c->ws + c->L.qr : nullptr;
 
+  c->mark(0, st);
   launch_append(D, q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
+  c->mark(1, st);
   const void* qx = D.rope ? qr : q;
   const void* Kx = D.rope ? A.Kr : A.K;
   if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
   else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
+  c->mark(2, st);
   run_score(c, q, k, v, T, scores_in ? nullptr : A.S, c->n_c, scores_out, st);
   if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st);
+  c->mark(3, st);
 
   const int L = c->n_c + T;
   if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
-  else c->n_c = L;
+  else { c->n_c = L; c->mark(4, st); }
+  c->mark(5, st);
+  if (c->prof_calls < c->prof_max) c->prof_calls++;
   c->seen += T;
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
 }
@@ -270,7 +283,49 @@ int locret_cache_view(const locret_ctx* c, const void** K, const void** V, const
   return LOCRET_OK;
 }
 
-void locret_destroy(locret_ctx* c) { delete c; }
+static void free_events(locret_ctx* c) {
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  c->ev.clear();
+  c->prof_max = c->prof_calls = 0;
+}
+
+int locret_profile_enable(locret_ctx* c, int32_t max_calls) {
+  if (!c || max_calls < 0 || max_calls > 65536) return LOCRET_EINVAL;
+  free_events(c);
+  if (max_calls == 0) return LOCRET_OK;
+  const size_t n = (size_t)max_calls * (LOCRET_PROF_STAGES + 1);
+  c->ev.reserve(n);
+  for (size_t i = 0; i < n; ++i) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) { free_events(c); return LOCRET_EHIP; }
+    c->ev.push_back(e);
+  }
+  c->prof_max = max_calls;
+  return LOCRET_OK;
+}
+
+int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
+  if (!c || !stage_ms || !n_calls) return LOCRET_EINVAL;
+  for (int s = 0; s < LOCRET_PROF_STAGES; ++s) stage_ms[s] = 0.0;
+  *n_calls = c->prof_calls;
+  for (int i = 0; i < c->prof_calls; ++i) {
+    hipEvent_t* e = &c->ev[(size_t)i * (LOCRET_PROF_STAGES + 1)];
+    if (hipEventSynchronize(e[LOCRET_PROF_STAGES]) != hipSuccess) return LOCRET_EHIP;
+    for (int s = 0; s < LOCRET_PROF_STAGES; ++s) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, e[s], e[s + 1]) != hipSuccess) return LOCRET_EHIP;
+      stage_ms[s] += ms;
+    }
+  }
+  c->prof_calls = 0;
+  return LOCRET_OK;
+}
+
+void locret_destroy(locret_ctx* c) {
+  if (!c) return;
+  free_events(c);
+  delete c;
+}
 
 const char* locret_strerror(int code) {
   switch (code) {
