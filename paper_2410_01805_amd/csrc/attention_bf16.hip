@@ -18,10 +18,12 @@
 // exchange with lane^32, and P^T leaves the accumulator already in B-operand order provided the
 // V^T tile stores its keys in the matching order (each group of 16 keys as 0-3, 8-11, 4-7, 12-15).
 //
-// K tile in LDS: [64 keys][D + 8] (16-byte pad: conflict-free 16-byte row reads).
-// V^T tile in LDS: [D][64 keys], transposed on the way in by 4x8 register blocks, 16-byte chunks
-// XOR-swizzled by (row ^ row>>3) & 7 so that both the transposing writes and the row reads spread
-// over the banks.  Tiles are double buffered through registers: one barrier per 64 keys.
+// K tile in LDS: [64 keys][D + 8]; V^T tile in LDS: [D][64 + 8], transposed on the way in by 4x8
+// register blocks.  The 16-byte row pad makes the stride an odd number of 16-byte chunks, so the
+// 16-byte row reads of consecutive lanes and the 8-byte transposing writes both spread over all
+// banks, and every LDS address is "per-thread base + compile-time offset".  Tiles are double
+// buffered through registers (one barrier per 64 keys); the tile loop is unrolled by two so the
+// buffer index is a compile-time constant, and only the last tile pays for bounds checks.
 #include "device_util.h"
 #include "kernels.h"
 
@@ -33,6 +35,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 64;   // keys per tile
+constexpr float RESCALE_LOG2 = 8.f;
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 x = {a, b};
@@ -40,32 +43,36 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return *(uint32_t*)&y;
 }
 
+// max over the two half-waves: after the swap one register holds the low half's value in both
+// halves and the other the high half's
+__device__ __forceinline__ float max_across_halves(float x) {
+  uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int D>
 struct AttnSmem {
   static constexpr int KSTR = D + 8;                 // bf16 elements per K row
+  static constexpr int VSTR = KT + 8;                // bf16 elements per V^T row
   bf16_t K[2][KT * KSTR];
-  bf16_t Vt[2][D * KT];
+  bf16_t Vt[2][D * VSTR];
 };
 
-// position (in bf16 elements) of key-quad kq (4 keys) of row `row` inside a V^T tile
-__device__ __forceinline__ int vt_quad_off(int row, int kq) {
-  int qg = kq & 3;
-  int kqp = (kq & ~3) | ((qg == 1) ? 2 : (qg == 2) ? 1 : qg);   // 0-3, 8-11, 4-7, 12-15 inside each 16
-  int chunk = (kqp >> 1) ^ ((row ^ (row >> 3)) & 7);
-  return row * KT + chunk * 8 + (kqp & 1) * 4;
-}
+template <int I> struct IntC { static constexpr int value = I; };
 
-template <int D, int QB>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
-                                                        const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
-                                                        int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                        int hpw, int n_hgroups, int n_ttiles) {
+template <int D, int QB, int WPE>
+__global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
+                                                             const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
+                                                             int Tn, int h, int g, int cap, int n_c, float c_log2,
+                                                             int hpw, int n_hgroups, int n_ttiles) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
   constexpr int NDB = D / 32;          // 32-row blocks of O^T
   constexpr int KCH = D / 8;           // 16-byte chunks per K row
   constexpr int K_LD = (KT * KCH) / 256;   // K chunks per thread per tile
   constexpr int V_BLK = (KT / 4) * KCH;    // 4-key x 8-dim blocks per V tile
   constexpr int KSTR = AttnSmem<D>::KSTR;
+  constexpr int VSTR = AttnSmem<D>::VSTR;
   __shared__ AttnSmem<D> sm;
 
   const int tid = threadIdx.x;
@@ -91,12 +98,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   const int TW = wph * 32 * QB;                // tokens per workgroup
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;     // query head of this wavefront
-  const int m = j / g;
+  const int m = (hgroup * hpw) / g;            // KV head: the same for all four wavefronts (blockIdx only)
   const int tw0 = t0 + (wave % wph) * 32 * QB; // first token of this wavefront
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;      // slots the workgroup stages
   const int n_tiles = (n_keys + KT - 1) / KT;
-  const int wave_last_slot = n_c + min(Tn - 1, tw0 + 32 * QB - 1);   // < 0 never: tw0 may exceed Tn
+  const int wave_last_slot = n_c + min(Tn - 1, tw0 + 32 * QB - 1);
 
   const bf16_t* Kb = Kx + (int64_t)m * cap * D;
   const bf16_t* Vb = V + (int64_t)m * cap * D;
@@ -122,38 +129,59 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-  // ---- staging registers -------------------------------------------------------------------
+  // ---- staging: a K tile is one contiguous block of KT*KCH 16-byte chunks; thread takes chunks
+  // ---- tid + 256 i.  A V tile is cut into 4-key x 8-dim blocks, one per thread. -----------------
   uint4 kreg[K_LD];
   uint4 vreg[4];
-  const int vblk = tid;                        // one 4-key x 8-dim block per thread (if < V_BLK)
-  const int v_kq = vblk & 15;                  // key quad: fastest over lanes -> LDS-friendly writes
-  const int v_d8 = vblk >> 4;                  // 8-dim column group
+  const int v_kq = tid & 15;                   // key quad: fastest over lanes -> contiguous LDS writes
+  const int v_d8 = tid >> 4;                   // 8-dim column group
+  const bool v_on = tid < V_BLK;
+  // Tiles are fetched with buffer loads whose descriptor covers exactly the slots this
+  // workgroup may stage: a read past them returns zero, so the last (partial) tile needs no
+  // branch and no load ever waits on a predicate.
+  int k_go[K_LD];                              // byte offset of chunk tid + 256 i inside a K tile
+#pragma unroll
+  for (int i = 0; i < K_LD; ++i) k_go[i] = (tid + 256 * i) * 16;
+  const int v_go = ((v_kq * 4) * D + v_d8 * 8) * 2;                      // + i*D*2
+  int k_st[K_LD];                              // LDS element offset of each staged K chunk
+#pragma unroll
+  for (int i = 0; i < K_LD; ++i) {
+    int c = tid + 256 * i;
+    k_st[i] = (c / KCH) * KSTR + (c % KCH) * 8;
+  }
+  // V^T destination of this thread's block: rows v_d8*8 + e, key-quad position with the keys of
+  // each group of 16 stored as 0-3, 8-11, 4-7, 12-15
+  const int v_qg = v_kq & 3;
+  const int v_kqp = (v_kq & ~3) | ((v_qg == 1) ? 2 : (v_qg == 2) ? 1 : v_qg);
+  const int v_st = (v_d8 * 8) * VSTR + v_kqp * 4;
+  // fragment read bases
+  const int k_rd = n32 * KSTR + hi * 8;        // + kb*32*KSTR + ks*16
+  const int v_rd = n32 * VSTR + hi * 8;        // + db*32*VSTR + kc*16
 
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   auto load_tile = [&](int tile) {
-    const int base = tile * KT;
+    const int left = max(n_keys - tile * KT, 0) * (D * 2);               // valid bytes from this tile on
+    const int64_t toff = (int64_t)tile * (KT * D);
+    __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + toff), 0, left, 0x00020000);
+    __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc((void*)(Vb + toff), 0, left, 0x00020000);
 #pragma unroll
     for (int i = 0; i < K_LD; ++i) {
-      int c = tid + 256 * i;
-      int row = c / KCH, col = c % KCH;
-      int slot = base + row;
-      kreg[i] = (slot < n_keys) ? *(const uint4*)(Kb + (int64_t)slot * D + col * 8) : make_uint4(0, 0, 0, 0);
+      u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(kr, k_go[i], 0, 0);
+      kreg[i] = make_uint4(x[0], x[1], x[2], x[3]);
     }
-    if (vblk < V_BLK) {
+    if (v_on) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        int slot = base + v_kq * 4 + i;
-        vreg[i] = (slot < n_keys) ? *(const uint4*)(Vb + (int64_t)slot * D + v_d8 * 8) : make_uint4(0, 0, 0, 0);
+        u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(vr, v_go + i * (D * 2), 0, 0);
+        vreg[i] = make_uint4(x[0], x[1], x[2], x[3]);
       }
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](auto bufc) {
+    constexpr int buf = decltype(bufc)::value;
 #pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      int c = tid + 256 * i;
-      int row = c / KCH, col = c % KCH;
-      *(uint4*)(&sm.K[buf][row * KSTR + col * 8]) = kreg[i];
-    }
-    if (vblk < V_BLK) {
+    for (int i = 0; i < K_LD; ++i) *(uint4*)(&sm.K[buf][k_st[i]]) = kreg[i];
+    if (v_on) {
       const uint32_t* r0 = (const uint32_t*)&vreg[0];
       const uint32_t* r1 = (const uint32_t*)&vreg[1];
       const uint32_t* r2 = (const uint32_t*)&vreg[2];
@@ -165,106 +193,138 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
         even.y = (r2[p] & 0xffffu) | (r3[p] << 16);
         odd.x = (r0[p] >> 16) | (r1[p] & 0xffff0000u);
         odd.y = (r2[p] >> 16) | (r3[p] & 0xffff0000u);
-        int row = v_d8 * 8 + 2 * p;
-        *(uint2*)(&sm.Vt[buf][vt_quad_off(row, v_kq)]) = even;
-        *(uint2*)(&sm.Vt[buf][vt_quad_off(row + 1, v_kq)]) = odd;
+        *(uint2*)(&sm.Vt[buf][v_st + (2 * p) * VSTR]) = even;
+        *(uint2*)(&sm.Vt[buf][v_st + (2 * p + 1) * VSTR]) = odd;
       }
     }
   };
 
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int buf = tile & 1;
+  // ---- one tile: S^T = K Q^T, online softmax, O^T += V^T P^T ------------------------------------
+  auto compute_tile = [&](auto bufc, int tile) {
+    constexpr int buf = decltype(bufc)::value;
     const int base = tile * KT;
-    if (tile + 1 < n_tiles) load_tile(tile + 1);
-
-    if (base <= wave_last_slot) {              // wave-uniform: later tiles hold nothing this wave sees
-      // ---- S^T = K Q^T ----------------------------------------------------------------------
-      f32x16 sacc[2][QB];
+    if (base > wave_last_slot) return;         // wave-uniform: nothing this wavefront may see
+    // K fragments are read a few steps ahead of the MFMAs that consume them, and the two 32-key
+    // blocks alternate so that consecutive MFMAs never wait on each other's accumulator.
+    f32x16 sacc[2][QB];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+    {
+      bf16x8 kf[NKS][2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16_t* kp = &sm.K[buf][(kb * 32 + n32) * KSTR + hi * 8];
+      for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          bf16x8 a = *(const bf16x8*)(kp + ks * 16);
+        for (int kb = 0; kb < 2; ++kb) kf[ks][kb] = *(const bf16x8*)(&sm.K[buf][k_rd + kb * 32 * KSTR + ks * 16]);
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
-        }
-      }
-      // ---- online softmax, per query block ------------------------------------------------------
-      uint4 pb[QB][4];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int limit = n_c + min(tw0 + qb * 32 + n32, Tn - 1);     // last visible slot of this lane's query
-        const bool need_mask = base + KT - 1 > n_c + tw0 + qb * 32;   // wave-uniform
-        if (need_mask) {
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              int slot = base + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
-              if (slot > limit) sacc[kb][qb][r] = -INFINITY;
-            }
-        }
-        float mx = -INFINITY;
+      for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[qb], mx);          // finite from tile 0 on (slot 0 is visible to all)
-        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c_log2);
-        const float mc = m_new * c_log2;
-        m_run[qb] = m_new;
-        float psum = 0.f;
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+      constexpr int AHEAD = 6;                      // fragments in flight
+      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          float p[16];
+      for (int i = 0; i < 2 * NKS - AHEAD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, AHEAD * QB, 0);
+    }
+    uint4 pb[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      if (base + KT - 1 > n_c + tw0 + qb * 32) {                     // wave-uniform: tile crosses the diagonal
+        const int limit = n_c + min(tw0 + qb * 32 + n32, Tn - 1);    // last visible slot of this lane's query
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][r], c_log2, -mc));
-            psum += p[r];
+            int slot = base + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
+            if (slot > limit) sacc[kb][qb][r] = -INFINITY;
           }
-          pb[qb][kb * 2 + 0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
-                                          pack_bf16(p[6], p[7]));
-          pb[qb][kb * 2 + 1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
-                                          pack_bf16(p[14], p[15]));
-        }
-        l_run[qb] = l_run[qb] * alpha + psum;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
+      mx = max_across_halves(mx);
+      // Lazy rescale: the running max is raised (and O, l rescaled) only when some query of the
+      // wavefront would otherwise see a probability above 2^RESCALE_LOG2; until then the stale
+      // max keeps every exponent bounded and the rescale pass over the O registers is skipped.
+      const float m_new = fmaxf(m_run[qb], mx);          // finite from tile 0 on (slot 0 is visible to all)
+      if (__any((m_new - m_run[qb]) * c_log2 > RESCALE_LOG2)) {
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c_log2);
+        m_run[qb] = m_new;
+        l_run[qb] *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
       }
-      // ---- O^T += V^T P^T -----------------------------------------------------------------------
+      const float mc = m_run[qb] * c_log2;
+      float psum = 0.f;
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-        const int row = db * 32 + n32;
-        const int swz = (row ^ (row >> 3)) & 7;
-        const bf16_t* vp = &sm.Vt[buf][row * KT];
+      for (int kb = 0; kb < 2; ++kb) {
+        float p[16];
 #pragma unroll
-        for (int kc = 0; kc < 4; ++kc) {
-          bf16x8 a = *(const bf16x8*)(vp + (((kc * 2 + hi) ^ swz) * 8));
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][r], c_log2, -mc));
+          psum += p[r];
+        }
+        pb[qb][kb * 2 + 0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
+                                        pack_bf16(p[6], p[7]));
+        pb[qb][kb * 2 + 1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
+                                        pack_bf16(p[14], p[15]));
+      }
+      l_run[qb] += psum;
+    }
+    {
+      bf16x8 vf[4][NDB];
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) vf[kc][db] = *(const bf16x8*)(&sm.Vt[buf][v_rd + db * 32 * VSTR + kc * 16]);
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb)
-            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, *(const bf16x8*)&pb[qb][kc], oacc[db][qb], 0, 0, 0);
-        }
+            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kc][db], *(const bf16x8*)&pb[qb][kc], oacc[db][qb], 0, 0, 0);
+      constexpr int AHEAD = 6;
+      __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 1);
+#pragma unroll
+      for (int i = 0; i < 4 * NDB - AHEAD; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, QB, 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, AHEAD * QB, 1);
     }
+  };
 
-    if (tile + 1 < n_tiles) store_tile(buf ^ 1);
+  auto step = [&](auto bufc, int tile) {
+    constexpr int buf = decltype(bufc)::value;
+    if (tile + 1 < n_tiles) load_tile(tile + 1);
+    compute_tile(bufc, tile);
+    if (tile + 1 < n_tiles) store_tile(IntC<buf ^ 1>());
     __syncthreads();
+  };
+
+  load_tile(0);
+  store_tile(IntC<0>());
+  __syncthreads();
+  int tile = 0;
+  for (; tile + 1 < n_tiles; tile += 2) {
+    step(IntC<0>(), tile);
+    step(IntC<1>(), tile + 1);
   }
+  if (tile < n_tiles) step(IntC<0>(), tile);
 
   // ---- epilogue: O = O^T / l, lane holds 4 consecutive dims per (db, r/4) for its query -------------
 #pragma unroll
@@ -287,7 +347,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   }
 }
 
-template <int D, int QB>
+template <int D, int QB, int WPE>
 static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                         float scale, hipStream_t st) {
   const int g = Dm.g;
@@ -297,7 +357,7 @@ static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const voi
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_mfma_kernel<D, QB>), dim3(n_hgroups * n_ttiles), dim3(256), 0, st, (const bf16_t*)q,
+  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, WPE>), dim3(n_hgroups * n_ttiles), dim3(256), 0, st, (const bf16_t*)q,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
                      n_hgroups, n_ttiles);
 }
@@ -306,7 +366,7 @@ static int attn_qb() {
   static int qb = -1;
   if (qb < 0) {
     const char* e = getenv("LOCRET_ATTN_QB");
-    qb = (e && e[0] == '1') ? 1 : 2;
+    qb = (e && e[0] == '2') ? 2 : 1;
   }
   return qb;
 }
@@ -316,8 +376,8 @@ void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const 
   const int qb = attn_qb();
 #define LOCRET_CASE(DD)                                                          \
   case DD:                                                                       \
-    if (qb == 1) attn_launch<DD, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);       \
-    else attn_launch<DD, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);               \
+    if (qb == 1) attn_launch<DD, 1, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);    \
+    else attn_launch<DD, 2, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);            \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)
