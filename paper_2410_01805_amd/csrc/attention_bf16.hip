@@ -24,52 +24,22 @@
 // banks, and every LDS address is "per-thread base + compile-time offset".  Tiles are double
 // buffered through registers (one barrier per 64 keys); the tile loop is unrolled by two so the
 // buffer index is a compile-time constant, and only the last tile pays for bounds checks.
-#include "device_util.h"
+#include <string.h>
+
+#include "attn_common.h"
 #include "kernels.h"
 
 namespace locret {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-constexpr int KT = 64;   // keys per tile
-constexpr float RESCALE_LOG2 = 8.f;
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  f32x2 x = {a, b};
-  bf16x2 y = __builtin_convertvector(x, bf16x2);   // v_cvt_pk_bf16_f32, round to nearest even
-  return *(uint32_t*)&y;
-}
-
-// max over the two half-waves: after the swap one register holds the low half's value in both
-// halves and the other the high half's
-__device__ __forceinline__ float max_across_halves(float x) {
-  uint32_t u = __float_as_uint(x);
-  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-template <int D>
-struct AttnSmem {
-  static constexpr int KSTR = D + 8;                 // bf16 elements per K row
-  static constexpr int VSTR = KT + 8;                // bf16 elements per V^T row
-  bf16_t K[2][KT * KSTR];
-  bf16_t Vt[2][D * VSTR];
-};
-
-template <int I> struct IntC { static constexpr int value = I; };
-
-template <int D, int QB, int WPE>
-__global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
+template <int D, int QB, int NW, int WPE>
+__global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c, float c_log2,
                                                              int hpw, int n_hgroups, int n_ttiles) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
   constexpr int NDB = D / 32;          // 32-row blocks of O^T
   constexpr int KCH = D / 8;           // 16-byte chunks per K row
-  constexpr int K_LD = (KT * KCH) / 256;   // K chunks per thread per tile
+  constexpr int K_LD = (KT * KCH) / 256;   // K chunks per staging thread per tile
   constexpr int V_BLK = (KT / 4) * KCH;    // 4-key x 8-dim blocks per V tile
   constexpr int KSTR = AttnSmem<D>::KSTR;
   constexpr int VSTR = AttnSmem<D>::VSTR;
@@ -77,7 +47,7 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: everything derived from it is wave-uniform
   const int n32 = lane & 31;
   const int hi = lane >> 5;
 
@@ -94,7 +64,7 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
     tt = bid / n_hgroups;
   }
   tt = n_ttiles - 1 - tt;                      // longest key ranges first
-  const int wph = 4 / hpw;                     // wavefronts per head
+  const int wph = NW / hpw;                    // wavefronts per head
   const int TW = wph * 32 * QB;                // tokens per workgroup
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;     // query head of this wavefront
@@ -129,24 +99,31 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
-  // ---- staging: a K tile is one contiguous block of KT*KCH 16-byte chunks; thread takes chunks
-  // ---- tid + 256 i.  A V tile is cut into 4-key x 8-dim blocks, one per thread. -----------------
-  uint4 kreg[K_LD];
-  uint4 vreg[4];
-  const int v_kq = tid & 15;                   // key quad: fastest over lanes -> contiguous LDS writes
-  const int v_d8 = tid >> 4;                   // 8-dim column group
-  const bool v_on = tid < V_BLK;
+  // ---- staging: a K tile is one contiguous block of KT*KCH 16-byte chunks, 256 threads take
+  // ---- chunks st + 256 i; a V tile is cut into 4-key x 8-dim blocks, one per thread of 256.
+  // ---- With 4 wavefronts every thread does both; with 8, wavefronts 0-3 stage V and 4-7 stage K
+  // ---- (one register set serves either role).
+  constexpr bool SPLIT = NW == 8;
+  const bool do_k = !SPLIT || wave >= 4;
+  const bool do_v = !SPLIT || wave < 4;
+  const int st = tid & 255;
+  uint4 kreg[4];
+  uint4 vreg_own[SPLIT ? 1 : 4];
+  uint4* vreg = SPLIT ? kreg : vreg_own;
+  const int v_kq = st & 15;                    // key quad: fastest over lanes -> contiguous LDS writes
+  const int v_d8 = st >> 4;                    // 8-dim column group
+  const bool v_on = do_v && st < V_BLK;
   // Tiles are fetched with buffer loads whose descriptor covers exactly the slots this
   // workgroup may stage: a read past them returns zero, so the last (partial) tile needs no
   // branch and no load ever waits on a predicate.
   int k_go[K_LD];                              // byte offset of chunk tid + 256 i inside a K tile
 #pragma unroll
-  for (int i = 0; i < K_LD; ++i) k_go[i] = (tid + 256 * i) * 16;
+  for (int i = 0; i < K_LD; ++i) k_go[i] = (st + 256 * i) * 16;
   const int v_go = ((v_kq * 4) * D + v_d8 * 8) * 2;                      // + i*D*2
   int k_st[K_LD];                              // LDS element offset of each staged K chunk
 #pragma unroll
   for (int i = 0; i < K_LD; ++i) {
-    int c = tid + 256 * i;
+    int c = st + 256 * i;
     k_st[i] = (c / KCH) * KSTR + (c % KCH) * 8;
   }
   // V^T destination of this thread's block: rows v_d8*8 + e, key-quad position with the keys of
@@ -164,10 +141,12 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
     const int64_t toff = (int64_t)tile * (KT * D);
     __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + toff), 0, left, 0x00020000);
     __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc((void*)(Vb + toff), 0, left, 0x00020000);
+    if (do_k) {
 #pragma unroll
-    for (int i = 0; i < K_LD; ++i) {
-      u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(kr, k_go[i], 0, 0);
-      kreg[i] = make_uint4(x[0], x[1], x[2], x[3]);
+      for (int i = 0; i < K_LD; ++i) {
+        u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(kr, k_go[i], 0, 0);
+        kreg[i] = make_uint4(x[0], x[1], x[2], x[3]);
+      }
     }
     if (v_on) {
 #pragma unroll
@@ -179,8 +158,10 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
   };
   auto store_tile = [&](auto bufc) {
     constexpr int buf = decltype(bufc)::value;
+    if (do_k) {
 #pragma unroll
-    for (int i = 0; i < K_LD; ++i) *(uint4*)(&sm.K[buf][k_st[i]]) = kreg[i];
+      for (int i = 0; i < K_LD; ++i) *(uint4*)(&sm.K[buf][k_st[i]]) = kreg[i];
+    }
     if (v_on) {
       const uint32_t* r0 = (const uint32_t*)&vreg[0];
       const uint32_t* r1 = (const uint32_t*)&vreg[1];
@@ -347,37 +328,45 @@ __global__ __launch_bounds__(256, WPE) void attn_mfma_kernel(const bf16_t* __res
   }
 }
 
-template <int D, int QB, int WPE>
+template <int D, int QB, int NW, int WPE>
 static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                         float scale, hipStream_t st) {
   const int g = Dm.g;
-  const int hpw = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
-  const int wph = 4 / hpw;
+  const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
+  const int wph = NW / hpw;
   const int TW = wph * 32 * QB;
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, WPE>), dim3(n_hgroups * n_ttiles), dim3(256), 0, st, (const bf16_t*)q,
+  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, (const bf16_t*)q,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
                      n_hgroups, n_ttiles);
 }
 
-static int attn_qb() {
-  static int qb = -1;
-  if (qb < 0) {
-    const char* e = getenv("LOCRET_ATTN_QB");
-    qb = (e && e[0] == '2') ? 2 : 1;
+// LOCRET_ATTN_VARIANT: "w8" (default) 8 wavefronts per workgroup, one workgroup per CU;
+// "w4" 4 wavefronts, two workgroups per CU; "qb2" 4 wavefronts with 64 queries each;
+// "pipe" the software-pipelined kernel of attention_pipe.hip.
+static int attn_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("LOCRET_ATTN_VARIANT");
+    v = 0;
+    if (e && !strcmp(e, "w4")) v = 1;
+    if (e && !strcmp(e, "qb2")) v = 2;
+    if (e && !strcmp(e, "pipe")) v = 3;
   }
-  return qb;
+  return v;
 }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st) {
-  const int qb = attn_qb();
-#define LOCRET_CASE(DD)                                                          \
-  case DD:                                                                       \
-    if (qb == 1) attn_launch<DD, 1, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);    \
-    else attn_launch<DD, 2, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);            \
+  const int v = attn_variant();
+  if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
+#define LOCRET_CASE(DD)                                                               \
+  case DD:                                                                            \
+    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);       \
+    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);  \
+    else attn_launch<DD, 1, 8, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);              \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)

@@ -44,6 +44,9 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
 // slots <= n_c+t (Eq. 1).  Reference-grade VALU kernel, any storage type.
 void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                              int T, int n_c, float scale, hipStream_t st);
+// Software-pipelined bf16 MFMA kernel (d in {64, 96, 128}); false if the shape is not covered.
+bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
+                                int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st);
