@@ -43,7 +43,13 @@ def host(t: torch.Tensor) -> np.ndarray:
 # belongs to: an attention output row is one convex combination of value rows, so its error
 # scales with that row's magnitude (rows that see few keys are O(1), rows that average thousands
 # are O(0.01)); scores are compared against the scale of the whole tensor.
-def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", per_row: bool = False):
+# The tensor-wide bar max|d| <= 2e-2 max|ref| always applies.  The element-wise bar is widened by
+# `kappa` = the factor by which a workload scales some key norms (config 3 plants keys 4x): a logit
+# is c * sum q_i k_i with each factor rounded to bf16 after rotation, so its absolute error is about
+# 2^-8.5 |q||k| / sqrt(d) ~ 3e-3 * key scale, and that is the relative error of the probabilities of
+# exactly the keys that dominate such a row.
+def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", per_row: bool = False,
+                 kappa: float = 1.0):
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
     assert np.isfinite(got).all(), f"{what}: non-finite values from the GPU"
@@ -54,7 +60,7 @@ def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", p
         scale = np.abs(ref).max()
         assert diff.max() <= 2e-2 * scale, f"{what}: max |d|={diff.max():.3e} vs 2e-2*{scale:.3e}"
         rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True)) if per_row else np.sqrt(np.mean(ref ** 2))
-        bound = 2e-2 * np.abs(ref) + 2e-2 * rms
+        bound = max(1.0, kappa) * (2e-2 * np.abs(ref) + 2e-2 * rms)
     bad = diff > bound
     if bad.any():
         i = np.unravel_index(np.argmax(diff - bound), diff.shape)
