@@ -2,12 +2,23 @@
 //   S~[t][m] = sum_r SiLU( sum_c x[t][c] W1[c][r] ) W2[r][m],   x[t] = [q_t ; k_t ; v_t]
 //
 // The hidden pre-activations are formed transposed, H^T[r][t] = W1t[r][:] . x[t][:], with
-// v_mfma_f32_32x32x16_bf16 (A = rows of the transposed weight, B = token rows; both are contiguous
-// along the contraction, so LDS rows are read as 16-byte vectors).  The input row is never
-// materialised: each 16-byte piece of a token's row is fetched from q, k or v directly.
-// A workgroup owns 128 hidden units x 128 tokens; SiLU and the product with W2 run on the
-// accumulators, and the workgroup writes its partial score part[nb][m][t] (nb = hidden block);
-// partials are summed in a fixed order by a separate tiny kernel, so results are deterministic.
+// v_mfma_f32_32x32x16_bf16 (A = rows of the transposed weight, B = token rows; both contiguous
+// along the contraction).  A workgroup owns 128 hidden units x 128 tokens (2 x 2 wavefronts of
+// 64 x 64).  The input row is never materialised: each stage of 64 contraction elements lies inside
+// one of q, k, v and is fetched from that tensor directly.
+//
+// Operand staging goes global -> LDS without passing through registers (buffer_load ... lds,
+// 16 bytes per lane) into a ring of four stages, so three stages are always in flight: with one
+// workgroup of four wavefronts per CU it is this depth, not occupancy, that hides memory latency.
+// Such a load writes lane L's 16 bytes at LDS base + 16 L, so an instruction fills 8 rows of 128
+// bytes back to back; bank conflicts are avoided by permuting WHICH 16-byte chunk a lane fetches:
+// position c' of row r holds chunk c' ^ (r & 7), and a fragment read of logical chunk c goes to
+// position c ^ (r & 7).  Rows past the chunk (t >= T) fall outside the buffer descriptor and arrive
+// as zeros.
+//
+// SiLU and the product with W2 run on the accumulators; the workgroup writes its partial score
+// part[nb][m][t] (nb = hidden block) and a tiny kernel sums the partials in a fixed order, so the
+// scores are deterministic.
 #include "device_util.h"
 #include "kernels.h"
 
@@ -16,17 +27,16 @@ namespace locret {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int RT_M = 128;   // hidden units per workgroup
-constexpr int RT_N = 128;   // tokens per workgroup
-constexpr int RT_K = 64;    // contraction elements per stage
-constexpr int RT_STR = RT_K + 8;
+constexpr int RT_M = 128;      // hidden units per workgroup
+constexpr int RT_N = 128;      // tokens per workgroup
+constexpr int RT_K = 64;       // contraction elements per stage (128 bytes per row)
+constexpr int RT_STAGES = 4;
+constexpr int RT_TILE_B = RT_M * RT_K * 2;            // bytes of one operand tile (16 KB)
+constexpr int RT_STAGE_B = 2 * RT_TILE_B;             // A then B
 
 struct ScoreSmem {
   union {
-    struct {
-      bf16_t A[2][RT_M * RT_STR];
-      bf16_t B[2][RT_N * RT_STR];
-    } st;
+    unsigned char ring[RT_STAGES * RT_STAGE_B];       // 128 KB
     struct {
       float W2s[RT_M * 32];          // [hidden][m-chunk of up to 32]
       float red[2 * RT_N * 32];      // [wm][token][m-chunk]
@@ -34,14 +44,17 @@ struct ScoreSmem {
   };
 };
 
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
 __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, int Tn, int hd, int kvd,
                                                          const bf16_t* __restrict__ W1t,
                                                          const float* __restrict__ W2f, int K, int h_kv,
                                                          float* __restrict__ part, int part_T) {
-  __shared__ ScoreSmem sm;
+  __shared__ __attribute__((aligned(1024))) ScoreSmem sm;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, hi = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
   const int t0 = blockIdx.x * RT_N;
@@ -56,56 +69,102 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  // staging: 128 rows x 8 chunks of 16 bytes per operand per stage = 4 chunks per thread each
-  uint4 areg[4], breg[4];
-  auto load_stage = [&](int k0) {
+  // ---- loads: wavefront w fills rows w*32 .. w*32+31 of both tiles, 8 rows per instruction -------
+  const int l_row = lane >> 3;                           // row inside the instruction's 8 rows
+  const int l_csw = ((lane & 7) ^ l_row) * 16;           // byte offset of the chunk this lane fetches
+  const int a_vo = (wave * 32 + l_row) * (K * 2) + l_csw;   // + ii * 8 rows
+  const int b_row = wave * 32 + l_row;                   // + ii * 8
+  const int n_stages = K / RT_K;
+  const int q_stages = hd / RT_K, k_stages = kvd / RT_K;
+  const int rows_left = min(max(Tn - t0, 0), RT_N);    // valid token rows of this workgroup
+
+  auto issue = [&](int s, int buf) {
+    // past the last stage the descriptors are empty: the loads return zeros into a free buffer and
+    // keep the number of loads in flight constant for the wait counts below
+    const bool live = s < n_stages;
+    {
+      __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(W1t + (int64_t)r0 * K + (int64_t)s * RT_K), 0, live ? (RT_M * K * 2 - s * RT_K * 2) : 0, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int c = tid + 256 * i;
-      int row = c >> 3, col = c & 7;
-      areg[i] = *(const uint4*)(W1t + (int64_t)(r0 + row) * K + k0 + col * 8);
-      int t = t0 + row;
-      int cc = k0 + col * 8;                      // column of [q;k;v]; a chunk never straddles tensors
-      const bf16_t* src;
-      if (cc < hd) src = q + (int64_t)t * hd + cc;
-      else if (cc < hd + kvd) src = k + (int64_t)t * kvd + (cc - hd);
-      else src = v + (int64_t)t * kvd + (cc - hd - kvd);
-      breg[i] = (t < Tn) ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
+      for (int ii = 0; ii < 4; ++ii)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            ar, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + (wave * 4 + ii) * 1024), 16, a_vo + ii * 8 * (K * 2), 0, 0, 0);
     }
-  };
-  auto store_stage = [&](int buf) {
+    {
+      const bf16_t* src;
+      int rowb, col;
+      if (s < q_stages) { src = q; rowb = hd * 2; col = s * RT_K; }
+      else if (s < q_stages + k_stages) { src = k; rowb = kvd * 2; col = (s - q_stages) * RT_K; }
+      else { src = v; rowb = kvd * 2; col = (s - q_stages - k_stages) * RT_K; }
+      // the descriptor starts at (t0, col) and ends with the last valid row, so rows >= T read as zero
+      const int64_t span = (int64_t)rows_left * rowb - col * 2;
+      __amdgpu_buffer_rsrc_t br = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(src + (int64_t)t0 * (rowb / 2) + col), 0, (live && span > 0) ? (int)span : 0, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int c = tid + 256 * i;
-      int row = c >> 3, col = c & 7;
-      *(uint4*)(&sm.st.A[buf][row * RT_STR + col * 8]) = areg[i];
-      *(uint4*)(&sm.st.B[buf][row * RT_STR + col * 8]) = breg[i];
+      for (int ii = 0; ii < 4; ++ii)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (wave * 4 + ii) * 1024), 16,
+            (b_row + ii * 8) * rowb + l_csw, 0, 0, 0);
     }
   };
 
-  const int n_stages = K / RT_K;
-  load_stage(0);
-  store_stage(0);
-  __syncthreads();
-  for (int s = 0; s < n_stages; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < n_stages) load_stage((s + 1) * RT_K);
-    const bf16_t* ap = &sm.st.A[buf][(wm * 64 + n32) * RT_STR + hi * 8];
-    const bf16_t* bp = &sm.st.B[buf][(wn * 64 + n32) * RT_STR + hi * 8];
+  // ---- fragment reads: row (wave part + n32), logical chunk 2 ks + hi at position chunk ^ (row & 7)
+  int a_rd[4], b_rd[4];
 #pragma unroll
-    for (int ks = 0; ks < RT_K / 16; ++ks) {
-      bf16x8 a0 = *(const bf16x8*)(ap + ks * 16);
-      bf16x8 a1 = *(const bf16x8*)(ap + 32 * RT_STR + ks * 16);
-      bf16x8 b0 = *(const bf16x8*)(bp + ks * 16);
-      bf16x8 b1 = *(const bf16x8*)(bp + 32 * RT_STR + ks * 16);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
-    }
-    if (s + 1 < n_stages) store_stage(buf ^ 1);
-    __syncthreads();
+  for (int ks = 0; ks < 4; ++ks) {
+    const int pos = ((2 * ks + hi) ^ (n32 & 7)) * 16;
+    a_rd[ks] = (wm * 64 + n32) * 128 + pos;
+    b_rd[ks] = RT_TILE_B + (wn * 64 + n32) * 128 + pos;
   }
+
+  auto compute = [&](int buf) {
+    const unsigned char* base = sm.ring + buf * RT_STAGE_B;
+    bf16x8 af[4][2], bfr[4][2];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      af[ks][0] = *(const bf16x8*)(base + a_rd[ks]);
+      af[ks][1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
+      bfr[ks][0] = *(const bf16x8*)(base + b_rd[ks]);
+      bfr[ks][1] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][0], bfr[ks][0], acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][0], bfr[ks][1], acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][0], acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][1], acc[1][1], 0, 0, 0);
+    }
+    // issue order: 8 fragment reads ahead, then one MFMA per remaining read
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+  };
+
+  // one ring step: stage s is complete once at most 2 stages (16 loads of this wavefront) are still
+  // in flight; after the barrier every wavefront's part of stage s is in LDS and nobody reads the
+  // buffer of stage s-1 any more, which is where stage s+3 goes
+  auto step = [&](int s, int buf) {
+    // a bare barrier: __syncthreads() would first drain every load in flight (they count as
+    // memory writes), which is exactly what the ring is there to avoid
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+    issue(s + RT_STAGES - 1, (buf + RT_STAGES - 1) % RT_STAGES);
+    compute(buf);
+  };
+
+  issue(0, 0);
+  issue(1, 1);
+  issue(2, 2);
+  for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
+    step(s0, 0);
+    if (s0 + 1 < n_stages) step(s0 + 1, 1);
+    if (s0 + 2 < n_stages) step(s0 + 2, 2);
+    if (s0 + 3 < n_stages) step(s0 + 3, 3);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // trailing empty loads must land before LDS is reused
 
   // ---- epilogue: SiLU in place, then W2 in chunks of up to 32 KV heads ---------------------------
 #pragma unroll
@@ -119,7 +178,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
       }
   for (int m0 = 0; m0 < h_kv; m0 += 32) {
     const int mc = min(32, h_kv - m0);
-    __syncthreads();                               // staging buffers / previous chunk no longer read
+    __syncthreads();                               // ring / previous chunk no longer read
     for (int i = tid; i < RT_M * mc; i += 256) {
       int hh = i / mc, mm = i % mc;
       sm.ep.W2s[hh * 32 + mm] = W2f[(int64_t)(r0 + hh) * h_kv + m0 + mm];
@@ -155,7 +214,9 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 
 int score_parts_bf16(const Dims& D) {
   if (!D.bf16) return 0;
-  if (D.d_R % RT_M != 0 || D.K % RT_K != 0 || D.d % 8 != 0) return 0;
+  // stages must not straddle q / k / v, and byte offsets inside one operand panel must fit 31 bits
+  if (D.d_R % RT_M != 0 || (D.h * D.d) % RT_K != 0 || (D.h_kv * D.d) % RT_K != 0) return 0;
+  if ((int64_t)RT_M * D.K * 2 >= (1ll << 31) || (int64_t)RT_N * D.h * D.d * 2 >= (1ll << 31)) return 0;
   return D.d_R / RT_M;
 }
 
