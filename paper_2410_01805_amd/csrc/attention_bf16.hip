@@ -343,14 +343,17 @@ static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const voi
                      n_hgroups, n_ttiles);
 }
 
-// LOCRET_ATTN_VARIANT: "w8" (default) 8 wavefronts per workgroup, one workgroup per CU;
-// "w4" 4 wavefronts, two workgroups per CU; "qb2" 4 wavefronts with 64 queries each;
-// "pipe" the software-pipelined kernel of attention_pipe.hip.
+// LOCRET_ATTN_VARIANT selects a kernel for experiments: default "dma" (direct-to-LDS staging,
+// attention_dma.hip; head_dim 128 only, other head dims fall through to "w8"); "dma4" its
+// 4-wavefront form; "w8" register-staged, 8 wavefronts per workgroup; "w4" 4 wavefronts, two
+// workgroups per CU; "qb2" 4 wavefronts with 64 queries each; "pipe" attention_pipe.hip.
 static int attn_variant() {
   static int v = -1;
   if (v < 0) {
     const char* e = getenv("LOCRET_ATTN_VARIANT");
-    v = 0;
+    v = 4;
+    if (e && !strcmp(e, "w8")) v = 0;
+    if (e && !strcmp(e, "dma4")) v = 5;
     if (e && !strcmp(e, "w4")) v = 1;
     if (e && !strcmp(e, "qb2")) v = 2;
     if (e && !strcmp(e, "pipe")) v = 3;
@@ -362,6 +365,7 @@ void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const 
                            float scale, hipStream_t st) {
   const int v = attn_variant();
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
+  if (v >= 4 && launch_attention_bf16_dma(Dm, v - 4, q, Kx, V, out, T, n_c, scale, st)) return;
 #define LOCRET_CASE(DD)                                                               \
   case DD:                                                                            \
     if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);       \

@@ -47,6 +47,10 @@ void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const
 // Software-pipelined bf16 MFMA kernel (d in {64, 96, 128}); false if the shape is not covered.
 bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                                 int T, int n_c, float scale, hipStream_t st);
+// bf16 MFMA kernel with K/V staged global->LDS directly (d = 128 only); false if the shape is not
+// covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
+bool launch_attention_bf16_dma(const Dims& D, int variant, const void* q, const void* Kx, const void* V, void* out,
+                               int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st);
