@@ -23,6 +23,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 PEAK_F32_TFLOPS = 157.3
 
+# HBM bytes of one steady-state attention launch, from the two rocprofv3 counter runs summarised in
+# profiles/chunk_step_cfg3_llama_128k_hbm_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# factors the calibration pass gave).  Only valid for the workload it was measured on.
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 226.7e6}
+
 
 def attention_flops(w, n_c, T):
     """QK^T + PV over the keys each query really sees (cache + causal part of the chunk)."""
@@ -50,7 +55,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg3_llama_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=48, help="query rows per head in the oracle's attention sample")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB): the "
+                         "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="measured HBM bytes per steady-state attention launch (from the counter runs), "
+                         "reported as roofline.traffic")
+    ap.add_argument("--cpu-rows", type=int, default=600, help="query rows per head in the oracle's attention sample")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus above 1 is not supported (no collectives are built)",
@@ -96,6 +107,12 @@ def main():
     for i in range(W):
         step(i)
     torch.cuda.synchronize()
+    if args.calibrate:
+        x = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        y = torch.empty_like(x)
+        torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        del x, y
 
     # ---- timed region ---------------------------------------------------------------------------------
     B.locret_reset(layer.ctx)
@@ -129,7 +146,9 @@ def main():
     attn_tflops = fl_attn / (ms["attention"] * 1e-3) / 1e12
     roofline = {
         "kernel": "attention", "bound": "mfma", "achieved": round(attn_tflops, 2), "peak": peak, "unit": "TFLOP/s",
-        "frac": round(attn_tflops / peak, 4), "traffic": None,
+        "frac": round(attn_tflops / peak, 4),
+        "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_ATTENTION_TRAFFIC_BYTES.get(w.name),
+        "algorithmic_bytes_steady": (2 * w.h_kv * (w.b + w.B) + 2 * w.B * w.h) * w.d * (2 if w.dtype == "bf16" else 4),
         "avg_launch_ms": round(ms["attention"] / max(1, n_prof), 4),
         "flops_per_launch_steady": attention_flops(w, w.b, w.B),
     }
