@@ -154,7 +154,10 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
 }
 
 // ------------------------------------------------------------------------------------------------
-template <typename T>
+// Compaction: dst[m][r] = src[m][kept[m][r]].  A thread owns slot r (and VEC rotary pairs of it)
+// for ALL KV heads: the rotary table row of slot r is read once and reused for every head, and
+// the loads of HB heads are issued together before anything is stored (memory-level parallelism).
+template <typename T, int HB>
 __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                       const float* __restrict__ Ss, const int32_t* __restrict__ Ps,
                                                       T* __restrict__ Kd, T* __restrict__ Vd, T* __restrict__ Krd,
@@ -163,37 +166,63 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
                                                       int n_keep, int h_kv, int d, int cap,
                                                       const float2* __restrict__ tab, int rope) {
   constexpr int VEC = Vec16<T>::N;
+  typedef Vec16<T> V16;
+  typedef decltype(V16().raw) raw_t;
   const int half = d / 2;
   const int tpr = half / VEC;
   int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t row = gid / tpr;
-  int part = (int)(gid % tpr);
-  if (row >= (int64_t)h_kv * n_keep) return;
-  int m = (int)(row / n_keep);
-  int r = (int)(row % n_keep);
-  int src = kept[(int64_t)m * kept_stride + r];
-  int off = part * VEC;
-  int64_t srow = ((int64_t)m * cap + src) * d;
-  int64_t drow = ((int64_t)m * cap + r) * d;
-  typedef Vec16<T> V16;
-  V16 klo, khi, vlo, vhi;
-  klo.raw = *(const decltype(klo.raw)*)(Ks + srow + off);
-  khi.raw = *(const decltype(klo.raw)*)(Ks + srow + half + off);
-  vlo.raw = *(const decltype(klo.raw)*)(Vs + srow + off);
-  vhi.raw = *(const decltype(klo.raw)*)(Vs + srow + half + off);
-  *(decltype(klo.raw)*)(Kd + drow + off) = klo.raw;
-  *(decltype(klo.raw)*)(Kd + drow + half + off) = khi.raw;
-  *(decltype(klo.raw)*)(Vd + drow + off) = vlo.raw;
-  *(decltype(klo.raw)*)(Vd + drow + half + off) = vhi.raw;
+  const int r = (int)(gid / tpr);
+  const int part = (int)(gid % tpr);
+  if (r >= n_keep) return;
+  const int off = part * VEC;
+  float2 cs[VEC];
   if (rope) {
-    V16 olo, ohi;
-    rotate_pairs<T>(klo, khi, olo, ohi, tab + (int64_t)r * half + off);
-    *(decltype(klo.raw)*)(Krd + drow + off) = olo.raw;
-    *(decltype(klo.raw)*)(Krd + drow + half + off) = ohi.raw;
+    const float2* tr = tab + (int64_t)r * half + off;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) cs[i] = tr[i];
   }
-  if (part == 0) {
-    Sd[(int64_t)m * cap + r] = Ss[(int64_t)m * cap + src];
-    Pd[(int64_t)m * cap + r] = Ps[(int64_t)m * cap + src];
+  for (int m0 = 0; m0 < h_kv; m0 += HB) {
+    int src[HB];
+    V16 klo[HB], khi[HB], vlo[HB], vhi[HB];
+#pragma unroll
+    for (int u = 0; u < HB; ++u) {
+      const int m = min(m0 + u, h_kv - 1);          // spare iterations repeat the last head (stores are skipped)
+      src[u] = kept[(int64_t)m * kept_stride + r];
+    }
+#pragma unroll
+    for (int u = 0; u < HB; ++u) {
+      const int m = min(m0 + u, h_kv - 1);
+      const int64_t srow = ((int64_t)m * cap + src[u]) * d;
+      klo[u].raw = *(const raw_t*)(Ks + srow + off);
+      khi[u].raw = *(const raw_t*)(Ks + srow + half + off);
+      vlo[u].raw = *(const raw_t*)(Vs + srow + off);
+      vhi[u].raw = *(const raw_t*)(Vs + srow + half + off);
+    }
+#pragma unroll
+    for (int u = 0; u < HB; ++u) {
+      const int m = m0 + u;
+      if (m >= h_kv) break;
+      const int64_t drow = ((int64_t)m * cap + r) * d;
+      *(raw_t*)(Kd + drow + off) = klo[u].raw;
+      *(raw_t*)(Kd + drow + half + off) = khi[u].raw;
+      *(raw_t*)(Vd + drow + off) = vlo[u].raw;
+      *(raw_t*)(Vd + drow + half + off) = vhi[u].raw;
+      if (rope) {
+        V16 olo, ohi;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          float a = klo[u].get(i), b = khi[u].get(i);
+          olo.set(i, a * cs[i].x - b * cs[i].y);
+          ohi.set(i, b * cs[i].x + a * cs[i].y);
+        }
+        *(raw_t*)(Krd + drow + off) = olo.raw;
+        *(raw_t*)(Krd + drow + half + off) = ohi.raw;
+      }
+      if (part == 0) {
+        Sd[(int64_t)m * cap + r] = Ss[(int64_t)m * cap + src[u]];
+        Pd[(int64_t)m * cap + r] = Ps[(int64_t)m * cap + src[u]];
+      }
+    }
   }
 }
 
@@ -201,17 +230,18 @@ void launch_compact(const Dims& D, const CacheBuf& s, const CacheBuf& t, const i
                     int n_keep, const float2* tab, hipStream_t st) {
   const int vec = D.bf16 ? 8 : 4;
   const int tpr = (D.d / 2) / vec;
-  int64_t threads = (int64_t)D.h_kv * n_keep * tpr;
+  int64_t threads = (int64_t)n_keep * tpr;
   if (threads == 0) return;
   dim3 grid((unsigned)((threads + 255) / 256));
+  // two heads per batch: enough loads in flight per thread while registers still allow many wavefronts
   if (D.bf16)
-    hipLaunchKernelGGL(compact_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)s.K, (const bf16_t*)s.V, s.S,
-                       s.P, (bf16_t*)t.K, (bf16_t*)t.V, (bf16_t*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv,
-                       D.d, D.cap, tab, D.rope);
+    hipLaunchKernelGGL((compact_kernel<bf16_t, 2>), grid, dim3(256), 0, st, (const bf16_t*)s.K, (const bf16_t*)s.V,
+                       s.S, s.P, (bf16_t*)t.K, (bf16_t*)t.V, (bf16_t*)t.Kr, t.S, t.P, kept, kept_stride, n_keep,
+                       D.h_kv, D.d, D.cap, tab, D.rope);
   else
-    hipLaunchKernelGGL(compact_kernel<float>, grid, dim3(256), 0, st, (const float*)s.K, (const float*)s.V, s.S,
-                       s.P, (float*)t.K, (float*)t.V, (float*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv,
-                       D.d, D.cap, tab, D.rope);
+    hipLaunchKernelGGL((compact_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)s.K, (const float*)s.V, s.S,
+                       s.P, (float*)t.K, (float*)t.V, (float*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv, D.d,
+                       D.cap, tab, D.rope);
 }
 
 }  // namespace locret

@@ -46,6 +46,10 @@ CASES = [
     ("odd_chunks", dict(dtype="bf16", h=4, h_kv=2, d=128, N=5000, B=1100, b=2000, n_s=33), [1, 1100, 7, 64, 65, 1023, 1, 1100, 1100, 538], "specials"),
     ("paper_phi3_row", dict(dtype="bf16", h=2, h_kv=2, d=96, N=20000, B=3072, b=6000, n_s=2500), None, "normal"),
     ("paper_llama_row", dict(dtype="bf16", h=2, h_kv=1, d=128, N=24000, B=1024, b=16384, n_s=2500), None, "normal"),
+    # more candidates than the register-resident select holds: keys staged in LDS ...
+    ("keys_in_lds", dict(dtype="f32", h=1, h_kv=1, d=16, N=34000, B=2000, b=26000, n_s=100, rope=False), None, "ties"),
+    # ... and more than LDS holds: keys re-read from global memory in every pass
+    ("keys_in_global", dict(dtype="f32", h=1, h_kv=1, d=16, N=50000, B=2000, b=40000, n_s=7, rope=False), None, "specials"),
 ]
 
 
