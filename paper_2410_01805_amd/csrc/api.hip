@@ -218,12 +218,14 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   void* qr = D.rope ? c->ws + c->L.qr : nullptr;
 
+  // the head_dim-128 attention kernel rotates the queries itself: no rotated copy is written or read
+  const bool fused_q = c->mfma_attn && attention_bf16_rotates_q(D);
   c->mark(0, st);
-  launch_append(D, q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
+  launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
   c->mark(1, st);
-  const void* qx = D.rope ? qr : q;
+  const void* qx = (D.rope && !fused_q) ? qr : q;
   const void* Kx = D.rope ? A.Kr : A.K;
-  if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
+  if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st, fused_q ? tab : nullptr);
   else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
   c->mark(2, st);
   run_score(c, q, k, v, T, scores_in ? nullptr : A.S, c->n_c, scores_out, st);

@@ -361,11 +361,17 @@ static int attn_variant() {
   return v;
 }
 
+static bool dma_applies(const Dims& Dm) {
+  return attn_variant() >= 4 && Dm.d == 128 && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
+}
+
+bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && dma_applies(Dm); }
+
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                           float scale, hipStream_t st) {
+                           float scale, hipStream_t st, const float2* q_rot_tab) {
   const int v = attn_variant();
+  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
-  if (v >= 4 && launch_attention_bf16_dma(Dm, v - 4, q, Kx, V, out, T, n_c, scale, st)) return;
 #define LOCRET_CASE(DD)                                                               \
   case DD:                                                                            \
     if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);       \

@@ -40,7 +40,7 @@ constexpr int DM_TILE_B = KT * DM_D * 2;       // 16 KB per operand tile
 constexpr int DM_STAGE_B = 2 * DM_TILE_B;      // K then V
 
 template <int NW, int NSTAGE>
-__global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
+__global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                               const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                               int Tn, int h, int g, int cap, int n_c, float c_log2,
                                                               int hpw, int n_hgroups, int n_ttiles) {
@@ -94,6 +94,26 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
     const bf16_t* qp = q + ((int64_t)my_t * h + j) * D + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
+    if (tab != nullptr) {
+      // un-rotated queries: rotate to position n_c + t here (pairs (i, i + D/2) sit in fragments ks
+      // and ks + NKS/2 of the same lane), round to bf16 as the append kernel would have
+      const float2* tp = tab + (int64_t)(n_c + my_t) * (D / 2) + hi * 8;
+#pragma unroll
+      for (int ks = 0; ks < NKS / 2; ++ks) {
+        float lo[8], up[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 cs = tp[ks * 16 + e];
+          const float a = (float)qf[ks][e], b = (float)qf[ks + NKS / 2][e];
+          lo[e] = a * cs.x - b * cs.y;
+          up[e] = b * cs.x + a * cs.y;
+        }
+        uint4 pl = make_uint4(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(lo[4], lo[5]), pack_bf16(lo[6], lo[7]));
+        uint4 pu = make_uint4(pack_bf16(up[0], up[1]), pack_bf16(up[2], up[3]), pack_bf16(up[4], up[5]), pack_bf16(up[6], up[7]));
+        qf[ks] = __builtin_bit_cast(bf16x8, pl);
+        qf[ks + NKS / 2] = __builtin_bit_cast(bf16x8, pu);
+      }
+    }
   }
   f32x16 oacc[NDB];
 #pragma unroll
@@ -294,7 +314,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
 }
 
 template <int NW, int NSTAGE>
-static void dma_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
+static void dma_launch(const Dims& Dm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T, int n_c,
                        float scale, hipStream_t st) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
@@ -304,17 +324,18 @@ static void dma_launch(const Dims& Dm, const void* q, const void* Kx, const void
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_dma_kernel<NW, NSTAGE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st,
-                     (const bf16_t*)q, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
+                     (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
                      c_log2, hpw, n_hgroups, n_ttiles);
 }
 
+// `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
 // variant 0: 8 wavefronts, 4-stage ring (one workgroup per CU); 1: 4 wavefronts, 2-stage ring (two per CU)
-bool launch_attention_bf16_dma(const Dims& Dm, int variant, const void* q, const void* Kx, const void* V, void* out,
+bool launch_attention_bf16_dma(const Dims& Dm, int variant, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                                int T, int n_c, float scale, hipStream_t st) {
   if (Dm.d != DM_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
-  if (variant == 1) dma_launch<4, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);
-  else dma_launch<8, 4>(Dm, q, Kx, V, out, T, n_c, scale, st);
+  if (variant == 1) dma_launch<4, 2>(Dm, q, tab, Kx, V, out, T, n_c, scale, st);
+  else dma_launch<8, 4>(Dm, q, tab, Kx, V, out, T, n_c, scale, st);
   return true;
 }
 

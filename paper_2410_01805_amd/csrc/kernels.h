@@ -49,11 +49,14 @@ bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, co
                                 int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel with K/V staged global->LDS directly (d = 128 only); false if the shape is not
 // covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
-bool launch_attention_bf16_dma(const Dims& D, int variant, const void* q, const void* Kx, const void* V, void* out,
+bool launch_attention_bf16_dma(const Dims& D, int variant, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                                int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
-                           int T, int n_c, float scale, hipStream_t st);
+                           int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr);
+// True when launch_attention_bf16 takes un-rotated queries plus the rotary table for these
+// dimensions (the kernel rotates them itself); otherwise it expects rotated queries.
+bool attention_bf16_rotates_q(const Dims& D);
 
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
