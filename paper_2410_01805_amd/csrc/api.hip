@@ -94,10 +94,16 @@ struct locret_ctx {
   int have_weights;
   float scale;
   int mfma_attn, mfma_score;
-  std::vector<hipEvent_t> ev;   // profiling: (LOCRET_PROF_STAGES + 1) events per recorded call
+  // Selection and compaction depend on the scores only, and compaction writes the other cache copy,
+  // so in the chunk step they run on a stream of the library's own beside attention (which reads
+  // the live copy): forked after the retaining head, joined before the call's stream goes on.
+  hipStream_t side;
+  hipEvent_t ev_fork, ev_join;
+  int overlap;
+  std::vector<hipEvent_t> ev;   // profiling: a (begin, end) pair per stage per recorded call
   int prof_max, prof_calls;
-  void mark(int stage, hipStream_t st) {
-    if (prof_calls < prof_max) (void)hipEventRecord(ev[(size_t)prof_calls * (LOCRET_PROF_STAGES + 1) + stage], st);
+  void mark(int stage, int end, hipStream_t st) {
+    if (prof_calls < prof_max) (void)hipEventRecord(ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end], st);
   }
   CacheBuf buf(int i) const {
     CacheBuf b;
@@ -130,6 +136,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   locret_ctx* c = new (std::nothrow) locret_ctx();
   if (!c) return LOCRET_ENOMEM;
   c->cur = 0; c->n_c = 0; c->seen = 0; c->have_weights = 0; c->prof_max = 0; c->prof_calls = 0;
+  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0;
   c->cfg = *cfg;
   fill_dims(cfg, &c->D);
   make_layout(cfg, c->D, &c->L);
@@ -148,6 +155,22 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
     (void)hipGetLastError();
     delete c;
     return LOCRET_EHIP;
+  }
+  // LOCRET_OVERLAP=1 (read here, per context): run selection and compaction beside attention.
+  // Off by default: measured on config 3 it gains 1.6 % per step (the selection's 1024-thread
+  // workgroups do not fit on a CU next to an attention workgroup, so they start only when the first
+  // attention workgroups retire) and it blurs the per-stage timings.
+  const char* ov = getenv("LOCRET_OVERLAP");
+  c->overlap = ov && ov[0] == '1';
+  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
+  if (c->overlap) {
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      locret_destroy(c);
+      return LOCRET_EHIP;
+    }
   }
   *out = c;
   return LOCRET_OK;
@@ -191,13 +214,16 @@ static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, h
   const int ns = n_stab < L ? n_stab : L;
   CacheBuf A = c->buf(c->cur);
   int32_t* kept = (int32_t*)(c->ws + c->L.kept);
+  c->mark(3, 0, st);
   launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, kept, b, kept_idx_out, b, st);
-  c->mark(4, st);
+  c->mark(3, 1, st);
+  c->mark(4, 0, st);
   if (L > b) {
     CacheBuf B = c->buf(c->cur ^ 1);
     launch_compact(c->D, A, B, kept, b, n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
     c->cur ^= 1;
   }
+  c->mark(4, 1, st);
   c->n_c = n_keep;
 }
 
@@ -220,25 +246,46 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
 
   // the head_dim-128 attention kernel rotates the queries itself: no rotated copy is written or read
   const bool fused_q = c->mfma_attn && attention_bf16_rotates_q(D);
-  c->mark(0, st);
+  c->mark(0, 0, st);
   launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
-  c->mark(1, st);
+  c->mark(0, 1, st);
   const void* qx = (D.rope && !fused_q) ? qr : q;
   const void* Kx = D.rope ? A.Kr : A.K;
-  if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st, fused_q ? tab : nullptr);
-  else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, c->n_c, c->scale, st);
-  c->mark(2, st);
-  run_score(c, q, k, v, T, scores_in ? nullptr : A.S, c->n_c, scores_out, st);
-  if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st);
-  c->mark(3, st);
-
-  const int L = c->n_c + T;
-  if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
-  else { c->n_c = L; c->mark(4, st); }
-  c->mark(5, st);
+  const int n_c = c->n_c;
+  const int L = n_c + T;
+  auto attention = [&]() {
+    c->mark(1, 0, st);
+    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr);
+    else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st);
+    c->mark(1, 1, st);
+  };
+  auto scores = [&]() {
+    c->mark(2, 0, st);
+    run_score(c, q, k, v, T, scores_in ? nullptr : A.S, n_c, scores_out, st);
+    if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, n_c, nullptr, st);
+    c->mark(2, 1, st);
+  };
+  bool ok = true;
+  if (evict && c->overlap) {
+    scores();
+    ok = ok && hipEventRecord(c->ev_fork, st) == hipSuccess;
+    ok = ok && hipStreamWaitEvent(c->side, c->ev_fork, 0) == hipSuccess;
+    run_evict(c, L, n_stab, kept_idx_out, c->side);
+    ok = ok && hipEventRecord(c->ev_join, c->side) == hipSuccess;
+    attention();
+    ok = ok && hipStreamWaitEvent(st, c->ev_join, 0) == hipSuccess;
+  } else {
+    attention();
+    scores();
+    if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
+    else {
+      c->n_c = L;
+      c->mark(3, 0, st); c->mark(3, 1, st); c->mark(4, 0, st); c->mark(4, 1, st);
+    }
+  }
   if (c->prof_calls < c->prof_max) c->prof_calls++;
   c->seen += T;
-  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
+  return (hipGetLastError() == hipSuccess && ok) ? LOCRET_OK : LOCRET_EHIP;
 }
 
 int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, float* scores,
@@ -295,7 +342,7 @@ int locret_profile_enable(locret_ctx* c, int32_t max_calls) {
   if (!c || max_calls < 0 || max_calls > 65536) return LOCRET_EINVAL;
   free_events(c);
   if (max_calls == 0) return LOCRET_OK;
-  const size_t n = (size_t)max_calls * (LOCRET_PROF_STAGES + 1);
+  const size_t n = (size_t)max_calls * LOCRET_PROF_STAGES * 2;
   c->ev.reserve(n);
   for (size_t i = 0; i < n; ++i) {
     hipEvent_t e;
@@ -311,11 +358,11 @@ int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
   for (int s = 0; s < LOCRET_PROF_STAGES; ++s) stage_ms[s] = 0.0;
   *n_calls = c->prof_calls;
   for (int i = 0; i < c->prof_calls; ++i) {
-    hipEvent_t* e = &c->ev[(size_t)i * (LOCRET_PROF_STAGES + 1)];
-    if (hipEventSynchronize(e[LOCRET_PROF_STAGES]) != hipSuccess) return LOCRET_EHIP;
+    hipEvent_t* e = &c->ev[(size_t)i * LOCRET_PROF_STAGES * 2];
     for (int s = 0; s < LOCRET_PROF_STAGES; ++s) {
       float ms = 0.f;
-      if (hipEventElapsedTime(&ms, e[s], e[s + 1]) != hipSuccess) return LOCRET_EHIP;
+      if (hipEventSynchronize(e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;
+      if (hipEventElapsedTime(&ms, e[2 * s], e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;
       stage_ms[s] += ms;
     }
   }
@@ -326,6 +373,9 @@ int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
 void locret_destroy(locret_ctx* c) {
   if (!c) return;
   free_events(c);
+  if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   delete c;
 }
 

@@ -85,6 +85,23 @@ def test_teacher_forced_stream(kw):
     layer.close()
 
 
+@pytest.mark.parametrize("kw", [SMALL[0], SMALL[4]], ids=["f32_gqa", "bf16_llama_like"])
+def test_teacher_forced_stream_with_eviction_beside_attention(kw, monkeypatch):
+    # LOCRET_OVERLAP=1 is read when the context is created: selection and compaction then run on the
+    # library's own stream beside attention; results must not change
+    monkeypatch.setenv("LOCRET_OVERLAP", "1")
+    w = synth.tiny(**kw)
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    K, V, S, P = layer.cache_tensors()
+    torch.cuda.synchronize()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+        np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
+        np.testing.assert_array_equal(host(V[m]), o.V[m].astype(np.float32))
+        np.testing.assert_array_equal(S[m].cpu().numpy(), o.S[m])
+    layer.close()
+
+
 def test_ragged_chunks_and_algorithm1_last_chunk():
     w = synth.tiny(name="ragged", dtype="bf16", h=8, h_kv=2, d=128, N=1500, B=400, b=500, n_s=60, d_R=128)
     layer, o, _ = _run_stream(w, chunk_sizes=[1, 400, 33, 64, 65, 127, 400, 10, 400], last_chunk_unmasked=True)
