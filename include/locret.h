@@ -110,6 +110,21 @@ int locret_prefill_chunk(locret_ctx* ctx, const void* q, const void* k, const vo
                          int32_t n_stab, int32_t evict, const float* scores_in, void* attn_out,
                          float* scores_out, int32_t* kept_idx_out, void* stream);
 
+/* Decode step (Section 3.1, Eq. 1 with B = 1; the generation step that closes Algorithm 1): appends
+ * ONE token at slot n_c (position n_c, like a chunk token) and attends over the n_c + 1 retained
+ * units.  Never evicts: the cache grows by one unit, up to budget + chunk_max
+ * (LOCRET_ESTATE beyond).
+ * q [1][n_q_heads][head_dim], k, v [1][n_kv_heads][head_dim], attn_out [1][n_q_heads][head_dim]:
+ *            device pointers, 16-byte aligned, un-rotated inputs, caller-owned.
+ * with_score != 0: the retaining head scores the token as locret_score would, the score is stored
+ *            with the unit (a later chunk step may then evict it on its merits) and copied to
+ *            scores_out (NULL or float [n_kv_heads]); needs weights (LOCRET_ESTATE).
+ * with_score == 0: plain generation; the unit's stored score is NaN, which the selection order
+ *            ranks below every number, so a later evicting call drops such units first.
+ * Asynchronous on `stream`; no allocation, no synchronisation. */
+int locret_decode_step(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t with_score,
+                       void* attn_out, float* scores_out, void* stream);
+
 /* Retaining head alone (Section 3.3): scores[m][t] for T tokens; the cache is not touched. */
 int locret_score(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t T,
                  float* scores, void* stream);

@@ -22,7 +22,7 @@ LOCRET_F32, LOCRET_BF16 = 0, 1
 
 EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_reset", "locret_prefill_chunk",
-    "locret_score", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
+    "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
     "locret_destroy", "locret_strerror", "locret_profile_enable", "locret_profile_read",
 ]
 LOCRET_PROF_STAGES = 5
@@ -55,6 +55,8 @@ def _load() -> C.CDLL:
     lib.locret_prefill_chunk.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32p, vp, f32p, i32p, vp]
     lib.locret_score.restype = C.c_int
     lib.locret_score.argtypes = [vp, vp, vp, vp, i32, f32p, vp]
+    lib.locret_decode_step.restype = C.c_int
+    lib.locret_decode_step.argtypes = [vp, vp, vp, vp, i32, vp, f32p, vp]
     lib.locret_evict_compact.restype = C.c_int
     lib.locret_evict_compact.argtypes = [vp, f32p, vp, vp, i32, i32, i32p, vp]
     lib.locret_cache_len.restype = C.c_int32
@@ -141,6 +143,11 @@ def locret_prefill_chunk(ctx, q, k, v, T, n_stab, evict, scores_in, attn_out, sc
            "locret_prefill_chunk")
 
 
+def locret_decode_step(ctx, q, k, v, with_score, attn_out, scores_out=None, stream=None) -> None:
+    _check(lib.locret_decode_step(ctx, _ptr(q), _ptr(k), _ptr(v), 1 if with_score else 0, _ptr(attn_out),
+                                  _ptr(scores_out), _stream(stream)), "locret_decode_step")
+
+
 def locret_score(ctx, q, k, v, T, scores, stream=None) -> None:
     _check(lib.locret_score(ctx, _ptr(q), _ptr(k), _ptr(v), T, _ptr(scores), _stream(stream)), "locret_score")
 
@@ -225,6 +232,14 @@ class LocretLayer:
         sc = torch.empty((self.cfg.n_kv_heads, T), dtype=torch.float32, device=self.device)
         locret_score(self.ctx, q, k, v, T, sc)
         return sc
+
+    def decode_step(self, q, k, v, with_score=False):
+        """One generated token: q [1][h][d], k, v [1][h_kv][d] -> (attn_out [1][h][d], scores [h_kv] or None)."""
+        import torch
+        out = torch.empty_like(q)
+        sc = torch.empty((self.cfg.n_kv_heads,), dtype=torch.float32, device=self.device) if with_score else None
+        locret_decode_step(self.ctx, q, k, v, with_score, out, sc)
+        return out, sc
 
     def evict_compact(self, scores, k, v, n_stab):
         import torch

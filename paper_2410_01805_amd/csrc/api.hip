@@ -20,7 +20,7 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
   size_t K[2], V[2], Kr[2], S[2], P[2];
-  size_t qr, tab, W1t, W2f, part, kept, total;
+  size_t qr, tab, W1t, W2f, part, kept, dpart, total;
 };
 
 bool valid_head_dim(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
@@ -76,6 +76,7 @@ void make_layout(const locret_config* c, const Dims& D, Layout* L) {
   L->W2f = take((size_t)D.d_R * D.h_kv * sizeof(float));
   L->part = take((size_t)max_score_parts(D) * D.h_kv * c->chunk_max * sizeof(float));
   L->kept = take((size_t)D.h_kv * c->budget * sizeof(int32_t));
+  L->dpart = take((size_t)D.h * decode_max_splits(D) * (D.d + 2) * sizeof(float));
   L->total = off;
 }
 
@@ -286,6 +287,27 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   if (c->prof_calls < c->prof_max) c->prof_calls++;
   c->seen += T;
   return (hipGetLastError() == hipSuccess && ok) ? LOCRET_OK : LOCRET_EHIP;
+}
+
+int locret_decode_step(locret_ctx* c, const void* q, const void* k, const void* v, int32_t with_score,
+                       void* attn_out, float* scores_out, void* stream) {
+  if (!c || !q || !k || !v || !attn_out) return LOCRET_EINVAL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(attn_out)) return LOCRET_EALIGN;
+  if (with_score && !c->have_weights) return LOCRET_ESTATE;
+  if (c->n_c + 1 > c->D.cap) return LOCRET_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  const Dims& D = c->D;
+  CacheBuf A = c->buf(c->cur);
+  const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
+  void* qr = D.rope ? c->ws + c->L.qr : nullptr;
+  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st);
+  if (with_score) run_score(c, q, k, v, 1, A.S, c->n_c, scores_out, st);
+  else launch_set_score(A.S, D.cap, D.h_kv, c->n_c, nanf(""), st);
+  launch_decode_attention(D, D.rope ? qr : q, D.rope ? A.Kr : A.K, A.V, attn_out, c->n_c + 1, c->scale,
+                          (float*)(c->ws + c->L.dpart), st);
+  c->n_c += 1;
+  c->seen += 1;
+  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
 }
 
 int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, float* scores,

@@ -1,0 +1,238 @@
+// Decode step: attention of ONE new token over the retained cache (Eq. 1 with B = 1; the generate
+// step that closes Algorithm 1).  The work is a single pass over K and V of every KV head, so the
+// kernel is built for HBM bandwidth: no matrix cores, no LDS staging.
+//
+// Split-K over the key axis: workgroup (split, m) owns DEC_KEYS keys of KV head m and serves the
+// query heads of its group (G at a time).  A key row is spread over LPR lanes (16 bytes per lane,
+// padded to a power of two), so one load instruction of a wavefront fetches 64 / LPRP whole rows,
+// contiguous in memory.  Each lane keeps the query values of its own dims for G heads; a logit is G
+// short dot products plus a butterfly over the lanes of the row; the lanes of a row then share the
+// probability and accumulate p * v for their dims.  Online softmax with a lazily raised max as in
+// the prefill kernels, one decision per UN rows.  The (max, sum, vector) triples of the 16 or 32
+// row slots of a workgroup are merged through LDS, those of the splits by decode_merge_kernel.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace locret {
+
+constexpr int DEC_THREADS = 256;
+constexpr int DEC_UN = 4;               // rows per lane group between max decisions
+constexpr float DEC_RESCALE_LOG2 = 8.f;
+
+template <int X> struct Pow2Ceil { static constexpr int value = X <= 1 ? 1 : 2 * Pow2Ceil<(X + 1) / 2>::value; };
+template <> struct Pow2Ceil<1> { static constexpr int value = 1; };
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ Kx,
+                                                                  const T* __restrict__ V, int g, int g0, int cap,
+                                                                  int n_keys, int keys_per_wg, float c_log2,
+                                                                  float* __restrict__ part, int n_splits) {
+  constexpr int VEC = Vec16<T>::N;
+  constexpr int LPR = D / VEC;                       // lanes that hold data of one row
+  constexpr int LPRP = Pow2Ceil<LPR>::value;         // lanes reserved per row
+  constexpr int KPW = 64 / LPRP;                     // rows per wavefront per load
+  constexpr int NSETS = (DEC_THREADS / 64) * KPW;    // row slots per workgroup
+  constexpr int PW = D + 2;                          // floats per partial: vector, max, sum
+  typedef Vec16<T> V16;
+  typedef decltype(V16().raw) raw_t;
+  __shared__ float sets[NSETS * G * PW];
+
+  const int split = blockIdx.x, m = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPRP, grp = lane / LPRP;
+  const bool act = sub < LPR;
+  const int k0 = split * keys_per_wg;
+  const int k1 = min(n_keys, k0 + keys_per_wg);
+  const T* Kb = Kx + (int64_t)m * cap * D;
+  const T* Vb = V + (int64_t)m * cap * D;
+  const int off = (act ? sub : 0) * VEC;
+
+  float qv[G][VEC];
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    const int j = m * g + min(g0 + u, g - 1);        // spare heads repeat the last one (not written)
+    V16 x;
+    x.raw = *(const raw_t*)(q + (int64_t)j * D + off);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) qv[u][e] = act ? x.get(e) * c_log2 : 0.f;   // logits in log2 units
+  }
+  float o[G][VEC], mrun[G], lrun[G];
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    mrun[u] = -INFINITY;
+    lrun[u] = 0.f;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) o[u][e] = 0.f;
+  }
+
+  constexpr int BLK = (DEC_THREADS / 64) * DEC_UN * KPW;   // rows per workgroup iteration
+  for (int kb = k0; kb < k1; kb += BLK) {
+    V16 kf[DEC_UN], vf[DEC_UN];
+    bool valid[DEC_UN];
+#pragma unroll
+    for (int i = 0; i < DEC_UN; ++i) {
+      const int key = kb + (wave * DEC_UN + i) * KPW + grp;
+      valid[i] = key < k1;
+      const int64_t row = (int64_t)(valid[i] ? key : k0) * D + off;   // spare slots re-read the first row
+      kf[i].raw = *(const raw_t*)(Kb + row);
+      vf[i].raw = *(const raw_t*)(Vb + row);
+    }
+    float s[DEC_UN][G];
+#pragma unroll
+    for (int i = 0; i < DEC_UN; ++i)
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        float a = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a = fmaf(kf[i].get(e), qv[u][e], a);
+#pragma unroll
+        for (int x = 1; x < LPRP; x <<= 1) a += __shfl_xor(a, x, 64);
+        s[i][u] = valid[i] ? a : -INFINITY;
+      }
+    // one max decision per head for the UN rows of this lane group
+    float muse[G];
+    bool up_any = false;
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      float mx = s[0][u];
+#pragma unroll
+      for (int i = 1; i < DEC_UN; ++i) mx = fmaxf(mx, s[i][u]);
+      const float m_new = fmaxf(mrun[u], mx);
+      const bool up = (m_new - mrun[u]) > DEC_RESCALE_LOG2;   // also true from -inf to a number
+      muse[u] = up ? m_new : mrun[u];
+      up_any = up_any || up;
+    }
+    if (__any(up_any)) {
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const float alpha = (muse[u] == mrun[u]) ? 1.f : __builtin_amdgcn_exp2f(mrun[u] - muse[u]);
+        lrun[u] *= alpha;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[u][e] *= alpha;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < G; ++u) mrun[u] = muse[u];
+#pragma unroll
+    for (int i = 0; i < DEC_UN; ++i)
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const float p = valid[i] ? __builtin_amdgcn_exp2f(s[i][u] - muse[u]) : 0.f;
+        lrun[u] += p;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[u][e] = fmaf(p, vf[i].get(e), o[u][e]);
+      }
+  }
+
+  // ---- merge the row slots of the workgroup ----------------------------------------------------
+  const int set = wave * KPW + grp;
+  if (act) {
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      float* dst = sets + (set * G + u) * PW;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) dst[off + e] = o[u][e];
+      if (sub == 0) {
+        dst[D] = mrun[u];
+        dst[D + 1] = lrun[u];
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * PW; idx += DEC_THREADS) {
+    const int u = idx / PW, e = idx % PW;
+    if (g0 + u >= g) continue;
+    float M = -INFINITY;
+    for (int s2 = 0; s2 < NSETS; ++s2) M = fmaxf(M, sets[(s2 * G + u) * PW + D]);
+    float val;
+    if (e == D) {
+      val = M;
+    } else {
+      float acc = 0.f;
+      for (int s2 = 0; s2 < NSETS; ++s2) {
+        const float ms = sets[(s2 * G + u) * PW + D];
+        const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);   // empty slots carry nothing
+        acc = fmaf(w, sets[(s2 * G + u) * PW + e], acc);     // e == D + 1 merges the sums
+      }
+      val = acc;
+    }
+    const int j = m * g + g0 + u;
+    part[((int64_t)j * n_splits + split) * PW + e] = val;
+  }
+}
+
+// out[j][:] = sum_s w_s o_s / sum_s w_s l_s with w_s = 2^(m_s - max m)
+template <typename T>
+__global__ void decode_merge_kernel(const float* __restrict__ part, int n_splits, int d, T* __restrict__ out) {
+  const int j = blockIdx.x;
+  const int pw = d + 2;
+  const float* p = part + (int64_t)j * n_splits * pw;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[s * pw + d]);
+  for (int e = threadIdx.x; e < d; e += blockDim.x) {
+    float acc = 0.f, l = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+      const float w = __builtin_amdgcn_exp2f(p[s * pw + d] - M);
+      acc = fmaf(w, p[s * pw + e], acc);
+      l = fmaf(w, p[s * pw + d + 1], l);
+    }
+    Elem<T>::st(out + (int64_t)j * d + e, acc / l);
+  }
+}
+
+int decode_keys_per_split() { return 256; }
+
+int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() - 1) / decode_keys_per_split(); }
+
+template <typename T, int DD>
+static void decode_launch(const Dims& D, const T* q, const T* Kx, const T* V, T* out, int n_keys, float scale,
+                          float* part, hipStream_t st) {
+  const int kpw = decode_keys_per_split();
+  const int n_splits = (n_keys + kpw - 1) / kpw;
+  const float c_log2 = scale * 1.4426950408889634f;
+  const dim3 grid(n_splits, D.h_kv);
+  for (int g0 = 0; g0 < D.g; g0 += 4) {
+    const int left = D.g - g0;
+    if (left >= 3)
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 4>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
+                         kpw, c_log2, part, n_splits);
+    else if (left == 2)
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 2>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
+                         kpw, c_log2, part, n_splits);
+    else
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
+                         kpw, c_log2, part, n_splits);
+  }
+  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(128), 0, st, part, n_splits, D.d, out);
+}
+
+void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
+                             float scale, float* part, hipStream_t st) {
+#define LOCRET_DEC(DD)                                                                                              \
+  case DD:                                                                                                          \
+    if (D.bf16) decode_launch<bf16_t, DD>(D, (const bf16_t*)q, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out,  \
+                                          n_keys, scale, part, st);                                                 \
+    else decode_launch<float, DD>(D, (const float*)q, (const float*)Kx, (const float*)V, (float*)out, n_keys,      \
+                                  scale, part, st);                                                                 \
+    break;
+  switch (D.d) {
+    LOCRET_DEC(16)
+    LOCRET_DEC(32)
+    LOCRET_DEC(64)
+    LOCRET_DEC(96)
+    LOCRET_DEC(128)
+  }
+#undef LOCRET_DEC
+}
+
+// S[m][pos] = value for every KV head (marks a unit whose score was not computed)
+__global__ void set_score_kernel(float* S, int cap, int h_kv, int pos, float value) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m < h_kv) S[(int64_t)m * cap + pos] = value;
+}
+
+void launch_set_score(float* S, int cap, int h_kv, int pos, float value, hipStream_t st) {
+  hipLaunchKernelGGL(set_score_kernel, dim3((h_kv + 63) / 64), dim3(64), 0, st, S, cap, h_kv, pos, value);
+}
+
+}  // namespace locret

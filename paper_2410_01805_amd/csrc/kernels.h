@@ -58,6 +58,15 @@ void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const v
 // dimensions (the kernel rotates them itself); otherwise it expects rotated queries.
 bool attention_bf16_rotates_q(const Dims& D);
 
+// Decode step (Eq. 1 with B = 1): one query row per head (rotated if rope) over slots [0, n_keys).
+// `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.
+int decode_keys_per_split();
+int decode_max_splits(const Dims& D);
+void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
+                             float scale, float* part, hipStream_t st);
+// S[m][pos] = value for every KV head.
+void launch_set_score(float* S, int cap, int h_kv, int pos, float value, hipStream_t st);
+
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
 int score_parts_simple(const Dims& D);
