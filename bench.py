@@ -164,6 +164,29 @@ def main():
         "input_gen_s": round(t_gen, 1),
     }
 
+    # ---- decode step (next row of the scope table): one generated token over the full budget ----------
+    # the cache is at the budget after the timed region; 64 generated tokens, plain generation (no score)
+    n_dec = min(64, w.B)
+    q1 = chunks[0][0][:1].contiguous(); k1 = chunks[0][1][:1].contiguous(); v1 = chunks[0][2][:1].contiguous()
+    o1 = torch.empty_like(q1)
+    for _ in range(8):
+        B.locret_decode_step(layer.ctx, q1, k1, v1, 0, o1, None)
+    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_units = B.locret_cache_len(layer.ctx)
+    torch.cuda.synchronize()
+    d0.record()
+    for _ in range(n_dec):
+        B.locret_decode_step(layer.ctx, q1, k1, v1, 0, o1, None)
+    d1.record()
+    torch.cuda.synchronize()
+    dec_ms = d0.elapsed_time(d1) / n_dec
+    es = 2 if w.dtype == "bf16" else 4
+    dec_bytes = 2 * w.h_kv * (n_units + n_dec / 2) * w.d * es          # one pass over (rotated) K and V
+    dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
+    extra["decode_step"] = {"units": n_units, "ms_per_token": round(dec_ms, 4), "bound": "hbm",
+                            "achieved": round(dec_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4), "timed": "append + split-K attention + merge"}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, host_chunks, args.cpu_rows)

@@ -300,9 +300,8 @@ int locret_decode_step(locret_ctx* c, const void* q, const void* k, const void* 
   CacheBuf A = c->buf(c->cur);
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   void* qr = D.rope ? c->ws + c->L.qr : nullptr;
-  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st);
+  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st, /*mark_unscored=*/!with_score);
   if (with_score) run_score(c, q, k, v, 1, A.S, c->n_c, scores_out, st);
-  else launch_set_score(A.S, D.cap, D.h_kv, c->n_c, nanf(""), st);
   launch_decode_attention(D, D.rope ? qr : q, D.rope ? A.Kr : A.K, A.V, attn_out, c->n_c + 1, c->scale,
                           (float*)(c->ws + c->L.dpart), st);
   c->n_c += 1;

@@ -90,7 +90,8 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
                                                      int h_kv, int d, int cap, T* __restrict__ Kc,
                                                      T* __restrict__ Vc, T* __restrict__ Krc,
                                                      int32_t* __restrict__ Pc, T* __restrict__ qr,
-                                                     const float2* __restrict__ tab, int rope, int q_rows) {
+                                                     const float2* __restrict__ tab, int rope, int q_rows,
+                                                     float* __restrict__ S_unscored) {
   constexpr int VEC = Vec16<T>::N;
   const int half = d / 2;
   const int tpr = half / VEC;
@@ -132,12 +133,16 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
       *(decltype(lo.raw)*)(Krc + drow + off) = olo.raw;
       *(decltype(lo.raw)*)(Krc + drow + half + off) = ohi.raw;
     }
-    if (part == 0) Pc[(int64_t)m * cap + n_c + t] = seen + t;
+    if (part == 0) {
+      Pc[(int64_t)m * cap + n_c + t] = seen + t;
+      if (S_unscored) S_unscored[(int64_t)m * cap + n_c + t] = __uint_as_float(0x7fc00000u);   // NaN: ranks last
+    }
   }
 }
 
 void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c, int64_t seen,
-                   const CacheBuf& c, void* qr, const float2* tab, hipStream_t st) {
+                   const CacheBuf& c, void* qr, const float2* tab, hipStream_t st, bool mark_unscored) {
+  float* Su = mark_unscored ? c.S : nullptr;
   const int vec = D.bf16 ? 8 : 4;
   const int tpr = (D.d / 2) / vec;
   const int q_rows = (D.rope && q != nullptr) ? D.h : 0;
@@ -146,11 +151,11 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
   if (D.bf16)
     hipLaunchKernelGGL(append_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (bf16_t*)c.K, (bf16_t*)c.V,
-                       (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows);
+                       (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows, Su);
   else
     hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
                        (const float*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (float*)c.K, (float*)c.V,
-                       (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows);
+                       (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows, Su);
 }
 
 // ------------------------------------------------------------------------------------------------

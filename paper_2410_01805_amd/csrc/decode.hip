@@ -10,6 +10,8 @@
 // probability and accumulate p * v for their dims.  Online softmax with a lazily raised max as in
 // the prefill kernels, one decision per UN rows.  The (max, sum, vector) triples of the 16 or 32
 // row slots of a workgroup are merged through LDS, those of the splits by decode_merge_kernel.
+#include <stdlib.h>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -161,26 +163,65 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
   }
 }
 
-// out[j][:] = sum_s w_s o_s / sum_s w_s l_s with w_s = 2^(m_s - max m)
+// out[j][:] = sum_s w_s o_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).  One workgroup per head.
+// A separate launch on purpose: letting the last workgroup of a head merge behind a device-scope
+// fence was measured 3x slower than both kernels together (every workgroup then pays for making its
+// partials visible across the eight L2s), while a kernel boundary does that once.
+constexpr int DEC_MERGE_THREADS = 256;
 template <typename T>
-__global__ void decode_merge_kernel(const float* __restrict__ part, int n_splits, int d, T* __restrict__ out) {
-  const int j = blockIdx.x;
+__global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const float* __restrict__ part, int n_splits,
+                                                                         int d, T* __restrict__ out) {
+  __shared__ float red[2 * (DEC_MERGE_THREADS / 64)];
+  const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int pw = d + 2;
   const float* p = part + (int64_t)j * n_splits * pw;
-  float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[s * pw + d]);
-  for (int e = threadIdx.x; e < d; e += blockDim.x) {
-    float acc = 0.f, l = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float w = __builtin_amdgcn_exp2f(p[s * pw + d] - M);
-      acc = fmaf(w, p[s * pw + e], acc);
-      l = fmaf(w, p[s * pw + d + 1], l);
-    }
-    Elem<T>::st(out + (int64_t)j * d + e, acc / l);
+  float mx = -INFINITY;
+  for (int s = tid; s < n_splits; s += DEC_MERGE_THREADS) mx = fmaxf(mx, p[s * pw + d]);
+#pragma unroll
+  for (int x = 32; x >= 1; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x, 64));
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  float M = red[0];
+#pragma unroll
+  for (int i = 1; i < DEC_MERGE_THREADS / 64; ++i) M = fmaxf(M, red[i]);
+  float ls = 0.f;
+  for (int s = tid; s < n_splits; s += DEC_MERGE_THREADS)
+    ls = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + d + 1], ls);
+#pragma unroll
+  for (int x = 32; x >= 1; x >>= 1) ls += __shfl_xor(ls, x, 64);
+  if (lane == 0) red[DEC_MERGE_THREADS / 64 + wave] = ls;
+  __syncthreads();
+  float l = 0.f;
+#pragma unroll
+  for (int i = 0; i < DEC_MERGE_THREADS / 64; ++i) l += red[DEC_MERGE_THREADS / 64 + i];
+  const float inv = 1.f / l;
+  // thread (e, r): element e, splits r, r + R, ...; the R partial sums of an element meet in LDS
+  __shared__ float acc_s[DEC_MERGE_THREADS];
+  const int R = DEC_MERGE_THREADS / 128;       // d <= 128
+  const int e = tid % 128, r = tid / 128;
+  float a = 0.f;
+  if (e < d)
+    for (int s = r; s < n_splits; s += R) a = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a);
+  acc_s[tid] = a;
+  __syncthreads();
+  if (tid < d) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < R; ++i) t += acc_s[tid + i * 128];
+    Elem<T>::st(out + (int64_t)j * d + tid, t * inv);
   }
 }
 
-int decode_keys_per_split() { return 256; }
+// keys per workgroup; LOCRET_DEC_KEYS (a multiple of 64, read once) overrides it for experiments
+int decode_keys_per_split() {
+  static int v = 0;
+  if (v == 0) {
+    const char* e = getenv("LOCRET_DEC_KEYS");
+    const int x = e ? atoi(e) : 0;
+    v = (x >= 64 && x <= 65536 && x % 64 == 0) ? x : 256;
+  }
+  return v;
+}
 
 int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() - 1) / decode_keys_per_split(); }
 
@@ -203,7 +244,7 @@ static void decode_launch(const Dims& D, const T* q, const T* Kx, const T* V, T*
       hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
                          kpw, c_log2, part, n_splits);
   }
-  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(128), 0, st, part, n_splits, D.d, out);
+  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, part, n_splits, D.d, out);
 }
 
 void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
@@ -211,7 +252,7 @@ void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const
 #define LOCRET_DEC(DD)                                                                                              \
   case DD:                                                                                                          \
     if (D.bf16) decode_launch<bf16_t, DD>(D, (const bf16_t*)q, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out,  \
-                                          n_keys, scale, part, st);                                                 \
+                                          n_keys, scale, part, st);                                            \
     else decode_launch<float, DD>(D, (const float*)q, (const float*)Kx, (const float*)V, (float*)out, n_keys,      \
                                   scale, part, st);                                                                 \
     break;
@@ -223,16 +264,6 @@ void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const
     LOCRET_DEC(128)
   }
 #undef LOCRET_DEC
-}
-
-// S[m][pos] = value for every KV head (marks a unit whose score was not computed)
-__global__ void set_score_kernel(float* S, int cap, int h_kv, int pos, float value) {
-  const int m = blockIdx.x * blockDim.x + threadIdx.x;
-  if (m < h_kv) S[(int64_t)m * cap + pos] = value;
-}
-
-void launch_set_score(float* S, int cap, int h_kv, int pos, float value, hipStream_t st) {
-  hipLaunchKernelGGL(set_score_kernel, dim3((h_kv + 63) / 64), dim3(64), 0, st, S, cap, h_kv, pos, value);
 }
 
 }  // namespace locret

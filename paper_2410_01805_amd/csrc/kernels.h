@@ -37,8 +37,10 @@ void launch_prep_weights(const Dims& D, int expand, const void* W1, const void* 
 
 // Append the chunk at slots [n_c, n_c+T) of `c`: K, V copied, Kr = K rotated to n_c+t,
 // P = seen + t; qr [T][h][d] = q rotated to n_c+t (rope only; q may be NULL to skip).
+// mark_unscored: also store NaN as the score of the appended units (no score will be computed).
 void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c,
-                   int64_t seen, const CacheBuf& c, void* qr, const float2* tab, hipStream_t st);
+                   int64_t seen, const CacheBuf& c, void* qr, const float2* tab, hipStream_t st,
+                   bool mark_unscored = false);
 
 // Attention of T queries (already rotated if rope) over slots [0, n_c+T) of Kx/V, query t seeing
 // slots <= n_c+t (Eq. 1).  Reference-grade VALU kernel, any storage type.
@@ -64,8 +66,6 @@ int decode_keys_per_split();
 int decode_max_splits(const Dims& D);
 void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
                              float scale, float* part, hipStream_t st);
-// S[m][pos] = value for every KV head.
-void launch_set_score(float* S, int cap, int h_kv, int pos, float value, hipStream_t st);
 
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
