@@ -88,6 +88,15 @@ int locret_create(const locret_config* cfg, void* dev_workspace, size_t workspac
  * linear map).  W1, W2: device, layouts above.  Asynchronous on `stream`. */
 int locret_set_weights(locret_ctx* ctx, const void* W1, const void* W2, void* stream);
 
+/* Pinned prefix (Locret-Q, Section "Supporting Query-Driven Tasks": the query is placed at the start of
+ * the sequence so that every eviction sees it).  From the next evicting call on, the first n_pin units
+ * of the cache are kept whatever their scores, like stabilizers at the front; the rest of the budget
+ * is shared as before.  Units keep their order, so once the first n_pin tokens of a stream are in the
+ * cache they stay in slots 0 .. n_pin-1.  Where the last n_stab units and the prefix would overlap
+ * (short lists) the stabilizers are counted first.  0 <= n_pin <= budget (LOCRET_EINVAL); an evicting
+ * call with n_stab + n_pin > budget returns LOCRET_EINVAL.  Default 0; locret_reset keeps it. */
+int locret_set_pinned_prefix(locret_ctx* ctx, int32_t n_pin);
+
 /* Empties the cache (n_c = 0, tokens seen = 0).  Host-only. */
 int locret_reset(locret_ctx* ctx);
 

@@ -91,27 +91,30 @@ def retaining_head(q, k, v, W1, W2, rh_kv_expand: int = 0) -> np.ndarray:
 # stabilizer mask + top-b (Section 3.4, Algorithm 1)
 # ----------------------------------------------------------------------------
 
-def select_keep(scores: np.ndarray, budget: int, n_stab: int) -> np.ndarray:
+def select_keep(scores: np.ndarray, budget: int, n_stab: int, n_pin: int = 0) -> np.ndarray:
     """Indices (ascending) of the units kept out of the L concatenated scores of one KV head.
 
-    The last min(n_stab, L) entries are always kept; the rest of the budget goes to
-    the best of the others under (score descending, index ascending).
+    The last min(n_stab, L) entries are always kept; so are the first n_pin of the others (the
+    query tokens that Locret-Q puts at the start of the sequence so that every eviction sees them,
+    Section "Supporting Query-Driven Tasks"); the rest of the budget goes to the best of the
+    remaining ones under (score descending, index ascending).
     """
     s = np.asarray(scores, dtype=np.float32)
     L = s.shape[0]
     n_keep = min(L, budget)
     ns = min(n_stab, L)
-    if ns > n_keep:
-        raise ValueError("stabilizer length exceeds the budget")
-    n_cand = L - ns
-    cand = s[:n_cand].astype(np.float64)
+    npin = min(n_pin, L - ns)
+    if ns + npin > n_keep:
+        raise ValueError("stabilizers and pinned prefix exceed the budget")
+    n_cand = L - ns - npin
+    cand = s[npin:npin + n_cand].astype(np.float64)
     isnan = np.isnan(cand)
     neg = np.where(isnan, 0.0, -cand) + 0.0          # -0.0 + 0.0 = +0.0: the two zeros tie
     # lexsort: last key is the primary one.  NaN after all numbers, then larger score first,
     # then lower index first.
     order = np.lexsort((np.arange(n_cand), neg, isnan.astype(np.int8)))
-    top = order[: n_keep - ns]
-    kept = np.concatenate([np.sort(top), np.arange(n_cand, L)])
+    top = order[: n_keep - ns - npin] + npin
+    kept = np.concatenate([np.arange(npin), np.sort(top), np.arange(npin + n_cand, L)])
     return kept.astype(np.int64)
 
 
@@ -123,8 +126,9 @@ class LocretLayerOracle:
     """State = per-KV-head K, V (un-rotated), true scores and original token positions."""
 
     def __init__(self, h: int, h_kv: int, d: int, budget: int, W1, W2, rh_kv_expand: int = 0,
-                 rope: bool = False, theta: float = 10000.0, scale: float | None = None):
+                 rope: bool = False, theta: float = 10000.0, scale: float | None = None, n_pin: int = 0):
         assert h % h_kv == 0
+        self.n_pin = n_pin          # units at the start of the cache that are never evicted (Locret-Q)
         self.h, self.h_kv, self.d, self.g = h, h_kv, d, h // h_kv
         self.budget = budget
         self.W1 = np.asarray(W1, dtype=np.float64)
@@ -194,7 +198,7 @@ class LocretLayerOracle:
             Sc = np.concatenate([self.S[m], scores[m]])
             Pc = np.concatenate([self.P[m], self.seen + np.arange(T, dtype=np.int64)])
             if evict:
-                idx = select_keep(Sc, self.budget, n_stab)
+                idx = select_keep(Sc, self.budget, n_stab, self.n_pin)
             else:
                 idx = np.arange(Sc.shape[0], dtype=np.int64)
             self.K[m], self.V[m], self.S[m], self.P[m] = Kc[idx], Vc[idx], Sc[idx], Pc[idx]

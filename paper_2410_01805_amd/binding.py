@@ -21,7 +21,7 @@ LOCRET_OK, LOCRET_EINVAL, LOCRET_ESHAPE, LOCRET_EALIGN, LOCRET_ESTATE, LOCRET_EH
 LOCRET_F32, LOCRET_BF16 = 0, 1
 
 EXPORTS = [
-    "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_reset", "locret_prefill_chunk",
+    "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_set_pinned_prefix", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
     "locret_destroy", "locret_strerror", "locret_profile_enable", "locret_profile_read",
 ]
@@ -59,6 +59,8 @@ def _load() -> C.CDLL:
     lib.locret_decode_step.argtypes = [vp, vp, vp, vp, i32, vp, f32p, vp]
     lib.locret_evict_compact.restype = C.c_int
     lib.locret_evict_compact.argtypes = [vp, f32p, vp, vp, i32, i32, i32p, vp]
+    lib.locret_set_pinned_prefix.restype = C.c_int
+    lib.locret_set_pinned_prefix.argtypes = [vp, i32]
     lib.locret_cache_len.restype = C.c_int32
     lib.locret_cache_len.argtypes = [vp]
     lib.locret_tokens_seen.restype = C.c_int64
@@ -141,6 +143,10 @@ def locret_prefill_chunk(ctx, q, k, v, T, n_stab, evict, scores_in, attn_out, sc
     _check(lib.locret_prefill_chunk(ctx, _ptr(q), _ptr(k), _ptr(v), T, n_stab, evict, _ptr(scores_in),
                                     _ptr(attn_out), _ptr(scores_out), _ptr(kept_idx_out), _stream(stream)),
            "locret_prefill_chunk")
+
+
+def locret_set_pinned_prefix(ctx, n_pin: int) -> None:
+    _check(lib.locret_set_pinned_prefix(ctx, n_pin), "locret_set_pinned_prefix")
 
 
 def locret_decode_step(ctx, q, k, v, with_score, attn_out, scores_out=None, stream=None) -> None:
@@ -232,6 +238,9 @@ class LocretLayer:
         sc = torch.empty((self.cfg.n_kv_heads, T), dtype=torch.float32, device=self.device)
         locret_score(self.ctx, q, k, v, T, sc)
         return sc
+
+    def set_pinned_prefix(self, n_pin: int) -> None:
+        locret_set_pinned_prefix(self.ctx, n_pin)
 
     def decode_step(self, q, k, v, with_score=False):
         """One generated token: q [1][h][d], k, v [1][h_kv][d] -> (attn_out [1][h][d], scores [h_kv] or None)."""

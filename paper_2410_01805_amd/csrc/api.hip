@@ -93,6 +93,7 @@ struct locret_ctx {
   int n_c;          // units per head in the live copy
   int64_t seen;     // tokens appended so far
   int have_weights;
+  int n_pin;        // units at the start of the cache that no call evicts (Locret-Q's query prefix)
   float scale;
   int mfma_attn, mfma_score;
   // Selection and compaction depend on the scores only, and compaction writes the other cache copy,
@@ -137,7 +138,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   locret_ctx* c = new (std::nothrow) locret_ctx();
   if (!c) return LOCRET_ENOMEM;
   c->cur = 0; c->n_c = 0; c->seen = 0; c->have_weights = 0; c->prof_max = 0; c->prof_calls = 0;
-  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0;
+  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0; c->n_pin = 0;
   c->cfg = *cfg;
   fill_dims(cfg, &c->D);
   make_layout(cfg, c->D, &c->L);
@@ -187,6 +188,12 @@ int locret_set_weights(locret_ctx* c, const void* W1, const void* W2, void* stre
   return LOCRET_OK;
 }
 
+int locret_set_pinned_prefix(locret_ctx* c, int32_t n_pin) {
+  if (!c || n_pin < 0 || n_pin > c->cfg.budget) return LOCRET_EINVAL;
+  c->n_pin = n_pin;
+  return LOCRET_OK;
+}
+
 int locret_reset(locret_ctx* c) {
   if (!c) return LOCRET_EINVAL;
   c->n_c = 0;
@@ -213,10 +220,11 @@ static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, h
   const int b = c->cfg.budget;
   const int n_keep = L < b ? L : b;
   const int ns = n_stab < L ? n_stab : L;
+  const int npin = c->n_pin < L - ns ? c->n_pin : L - ns;     // the prefix covers what the stabilizers leave
   CacheBuf A = c->buf(c->cur);
   int32_t* kept = (int32_t*)(c->ws + c->L.kept);
   c->mark(3, 0, st);
-  launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, kept, b, kept_idx_out, b, st);
+  launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, npin, kept, b, kept_idx_out, b, st);
   c->mark(3, 1, st);
   c->mark(4, 0, st);
   if (L > b) {
@@ -233,6 +241,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
                          int32_t* kept_idx_out, void* stream) {
   if (!c || !q || !k || !v || !attn_out) return LOCRET_EINVAL;
   if (n_stab < 0 || n_stab > c->cfg.budget) return LOCRET_EINVAL;
+  if (evict && n_stab + c->n_pin > c->cfg.budget) return LOCRET_EINVAL;
   if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(attn_out) || misaligned(scores_in) ||
       misaligned(scores_out) || misaligned(kept_idx_out))
@@ -322,7 +331,7 @@ int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int
 int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k, const void* v, int32_t T,
                          int32_t n_stab, int32_t* kept_idx_out, void* stream) {
   if (!c || !chunk_scores || !k || !v) return LOCRET_EINVAL;
-  if (n_stab < 0 || n_stab > c->cfg.budget) return LOCRET_EINVAL;
+  if (n_stab < 0 || n_stab + c->n_pin > c->cfg.budget) return LOCRET_EINVAL;
   if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
   if (misaligned(chunk_scores) || misaligned(k) || misaligned(v) || misaligned(kept_idx_out)) return LOCRET_EALIGN;
   if (c->n_c + T > c->D.cap) return LOCRET_ESTATE;

@@ -80,10 +80,10 @@ void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* 
 void launch_score_reduce(const float* part, int n_parts, int part_stride_T, int h_kv, int T, float* S,
                          int cap, int n_c, float* out, hipStream_t st);
 
-// Stabilizer-masked top-k per KV head over S[m][0..L): keeps the last n_stab and the best
-// (n_keep - n_stab) of the rest (score desc, index asc); kept[m][0..n_keep) ascending.
-// kept2 (optional, row stride stride2) receives a copy.
-void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int32_t* kept,
+// Stabilizer-masked top-k per KV head over S[m][0..L): keeps the first n_pin, the last n_stab and the
+// best (n_keep - n_stab - n_pin) of the rest (score desc, index asc); kept[m][0..n_keep) ascending.
+// Requires n_pin + n_stab <= min(L, n_keep).  kept2 (optional, row stride stride2) receives a copy.
+void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int n_pin, int32_t* kept,
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st);
 
 // dst[m][r] = src[m][kept[m][r]] for K, V, S, P; dst.Kr[m][r] = K rotated to position r.

@@ -1,4 +1,6 @@
-// Stabilizer-masked top-k per KV head (Section 3.4; Algorithm 1: "+inf on the last n_s, top-b").
+// Stabilizer-masked top-k per KV head (Section 3.4; Algorithm 1: "+inf on the last n_s, top-b"),
+// with an optional pinned prefix (the first n_pin units are kept as well: Locret-Q keeps the query,
+// placed at the start of the sequence, visible to every eviction).
 //
 // One 1024-thread workgroup per KV head.  Scores become order-preserving 32-bit keys (NaN lowest,
 // -0 == +0) held in LDS; a 4-pass, 8-bit-per-pass radix select finds the key tau of the k-th best
@@ -35,7 +37,8 @@ constexpr int SEL_HDR = 256 * SEL_REP + 256 + 128;   // words of LDS before the 
 
 template <bool IN_LDS>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ S, int cap, int L,
-                                                             int n_keep, int n_stab, int32_t* __restrict__ kept,
+                                                             int n_keep, int n_stab, int n_pin,
+                                                             int32_t* __restrict__ kept,
                                                              int kept_stride, int32_t* __restrict__ kept2,
                                                              int stride2) {
   extern __shared__ uint32_t smem[];
@@ -46,12 +49,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
   uint32_t* keys = smem + SEL_HDR;
 
   const int m = blockIdx.x;
-  const float* s = S + (int64_t)m * cap;
+  const float* s = S + (int64_t)m * cap + n_pin;   // candidate c is unit n_pin + c
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int n_cand = L - n_stab;
-  const int kk = n_keep - n_stab;      // candidates to keep, 0 <= kk <= n_cand
+  const int n_cand = L - n_stab - n_pin;
+  const int kk = n_keep - n_stab - n_pin;          // candidates to keep, 0 <= kk <= n_cand
 
   if (IN_LDS)
     for (int i = tid; i < n_cand; i += SEL_THREADS) keys[i] = score_key(s[i]);
@@ -136,8 +139,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
   uint32_t run_gt = 0, run_eq = 0;
   for (int w = 0; w < wave; ++w) { run_gt += wsum[w]; run_eq += wsum[SEL_WAVES + w]; }
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  int32_t* out = kept + (int64_t)m * kept_stride;
-  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 : nullptr;
+  // kept list: pinned prefix [0, n_pin), then the chosen candidates, then the stabilizers
+  int32_t* out = kept + (int64_t)m * kept_stride + n_pin;
+  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 + n_pin : nullptr;
+  for (int i = tid; i < n_pin; i += SEL_THREADS) {
+    out[i - n_pin] = i;
+    if (out2) out2[i - n_pin] = i;
+  }
   for (int base = w_lo; base < w_hi; base += 64) {
     int i = base + lane;
     uint32_t key = (i < w_hi) ? key_at(i) : 0u;
@@ -149,15 +157,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     bool keep = gt || (eq && eq_before < need_eq);
     if (keep) {
       uint32_t pos = gt_before + min(eq_before, need_eq);
-      out[pos] = i;
-      if (out2) out2[pos] = i;
+      out[pos] = n_pin + i;
+      if (out2) out2[pos] = n_pin + i;
     }
     run_gt += __popcll(bg);
     run_eq += __popcll(be);
   }
-  for (int i = n_cand + tid; i < L; i += SEL_THREADS) {
-    out[kk + (i - n_cand)] = i;
-    if (out2) out2[kk + (i - n_cand)] = i;
+  for (int i = n_cand + tid; i < L - n_pin; i += SEL_THREADS) {
+    out[kk + (i - n_cand)] = n_pin + i;
+    if (out2) out2[kk + (i - n_cand)] = n_pin + i;
   }
 }
 
@@ -165,7 +173,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
 // Register-resident variant: MAXR keys per thread.
 template <int MAXR>
 __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __restrict__ S, int cap, int L,
-                                                                 int n_keep, int n_stab, int32_t* __restrict__ kept,
+                                                                 int n_keep, int n_stab, int n_pin,
+                                                                 int32_t* __restrict__ kept,
                                                                  int kept_stride, int32_t* __restrict__ kept2,
                                                                  int stride2) {
   __shared__ uint32_t hist[256 * SEL_REP];
@@ -173,12 +182,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __
   __shared__ uint32_t wsum[2 * SEL_WAVES];
   __shared__ uint32_t bc[2];
   const int m = blockIdx.x;
-  const float* s = S + (int64_t)m * cap;
+  const float* s = S + (int64_t)m * cap + n_pin;   // candidate c is unit n_pin + c
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int n_cand = L - n_stab;
-  const int kk = n_keep - n_stab;
+  const int n_cand = L - n_stab - n_pin;
+  const int kk = n_keep - n_stab - n_pin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;     // <= MAXR * 64 (checked by the host)
   const int w_lo = wave * wseg;
   const int w_hi = min(n_cand, w_lo + wseg);
@@ -263,8 +272,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __
   uint32_t run_gt = 0, run_eq = 0;
   for (int w = 0; w < wave; ++w) { run_gt += wsum[w]; run_eq += wsum[SEL_WAVES + w]; }
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  int32_t* out = kept + (int64_t)m * kept_stride;
-  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 : nullptr;
+  // kept list: pinned prefix [0, n_pin), then the chosen candidates, then the stabilizers
+  int32_t* out = kept + (int64_t)m * kept_stride + n_pin;
+  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 + n_pin : nullptr;
+  for (int i = tid; i < n_pin; i += SEL_THREADS) {
+    out[i - n_pin] = i;
+    if (out2) out2[i - n_pin] = i;
+  }
 #pragma unroll
   for (int j = 0; j < MAXR; ++j) {
     const bool gt = j < nvalid && k[j] > tau;
@@ -274,21 +288,21 @@ __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __
     const uint32_t eq_before = run_eq + __popcll(be & lt_mask);
     if (gt || (eq && eq_before < need_eq)) {
       const uint32_t pos = gt_before + min(eq_before, need_eq);
-      out[pos] = first + j * 64;
-      if (out2) out2[pos] = first + j * 64;
+      out[pos] = n_pin + first + j * 64;
+      if (out2) out2[pos] = n_pin + first + j * 64;
     }
     run_gt += __popcll(bg);
     run_eq += __popcll(be);
   }
-  for (int i = n_cand + tid; i < L; i += SEL_THREADS) {
-    out[kk + (i - n_cand)] = i;
-    if (out2) out2[kk + (i - n_cand)] = i;
+  for (int i = n_cand + tid; i < L - n_pin; i += SEL_THREADS) {
+    out[kk + (i - n_cand)] = n_pin + i;
+    if (out2) out2[kk + (i - n_cand)] = n_pin + i;
   }
 }
 
 static int g_lds_limit = -1;   // bytes of dynamic LDS the in-LDS variant may use
 
-void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int32_t* kept,
+void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int n_pin, int32_t* kept,
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
   if (g_lds_limit < 0) {
     g_lds_limit = 64 * 1024;
@@ -298,25 +312,25 @@ void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_s
     else
       (void)hipGetLastError();
   }
-  const int n_cand = L - n_stab;
+  const int n_cand = L - n_stab - n_pin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
   if (wseg <= 12 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, kept,
+    hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, n_pin, kept,
                        kept_stride, kept2, stride2);
     return;
   }
   if (wseg <= 24 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, kept,
+    hipLaunchKernelGGL(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, n_pin, kept,
                        kept_stride, kept2, stride2);
     return;
   }
   size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);
   if (need <= (size_t)g_lds_limit)
     hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, S, cap, L, n_keep, n_stab,
-                       kept, kept_stride, kept2, stride2);
+                       n_pin, kept, kept_stride, kept2, stride2);
   else
     hipLaunchKernelGGL(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, S,
-                       cap, L, n_keep, n_stab, kept, kept_stride, kept2, stride2);
+                       cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2);
 }
 
 }  // namespace locret

@@ -46,28 +46,33 @@ def rank_key(score: float, pos: int):
     return (0, -score + 0.0, pos)
 
 
-def closed_form_kept(scores, n_seen: int, b: int, n_s: int):
+def closed_form_kept(scores, n_seen: int, b: int, n_s: int, n_pin: int = 0):
     """Kept original positions after n_seen tokens, for a constant stabilizer length:
     the most recent n_s tokens plus the best (b - n_s) of the earlier ones, taken over
     ALL earlier tokens (Appendix "Causal Importance Score Simulates a Cache Problem":
-    a unit once evicted never returns, so the running top-b equals the global one)."""
+    a unit once evicted never returns, so the running top-b equals the global one).
+    With a pinned prefix the first n_pin tokens of the stream are kept as well and the
+    competition is among the tokens between them and the stabilizers."""
     ns = min(n_s, n_seen)
+    npin = min(n_pin, n_seen - ns)
     n_keep = min(n_seen, b)
-    cand = sorted(range(n_seen - ns), key=lambda p: rank_key(float(scores[p]), p))
-    return sorted(cand[: n_keep - ns]) + list(range(n_seen - ns, n_seen))
+    cand = sorted(range(npin, n_seen - ns), key=lambda p: rank_key(float(scores[p]), p))
+    return list(range(npin)) + sorted(cand[: n_keep - ns - npin]) + list(range(n_seen - ns, n_seen))
 
 
-def simulate_algorithm1(scores, boundaries, b, n_s_per_chunk):
+def simulate_algorithm1(scores, boundaries, b, n_s_per_chunk, n_pin: int = 0):
     """Literal list-based run of the cache loop of Algorithm 1 for one head: returns the kept
     original positions after every chunk.  The +inf mask is applied to a copy, the stored
-    score stays the true one."""
+    score stays the true one.  A pinned prefix is masked the same way at the front; where the two
+    masks would overlap the stabilizers come first (the prefix only covers what they leave)."""
     cache = []  # list of (true_score, pos)
     hist = []
     start = 0
     for end, n_s in zip(boundaries, n_s_per_chunk):
         cache += [(float(scores[p]), p) for p in range(start, end)]
         L = len(cache)
-        masked = [(math.inf if i >= L - n_s else s, i) for i, (s, _) in enumerate(cache)]
+        npin = min(n_pin, L - min(n_s, L))
+        masked = [(math.inf if (i >= L - n_s or i < npin) else s, i) for i, (s, _) in enumerate(cache)]
         order = sorted(masked, key=lambda si: rank_key(si[0], si[1]))
         keep_slots = sorted(i for _, i in order[: min(L, b)])
         cache = [cache[i] for i in keep_slots]

@@ -15,9 +15,12 @@ from tests.gpu_util import DEV, assert_close, dev, host, make_layer, make_oracle
 pytestmark = pytest.mark.gpu
 
 
-def _run_stream(w, teacher_forced=True, chunk_sizes=None, last_chunk_unmasked=False, attn_rows=None):
+def _run_stream(w, teacher_forced=True, chunk_sizes=None, last_chunk_unmasked=False, attn_rows=None, n_pin=0):
     layer, W1, W2 = make_layer(w)
     o = make_oracle(w, W1, W2)
+    if n_pin:
+        o.n_pin = n_pin
+        layer.set_pinned_prefix(n_pin)
     lo = 0
     sizes = chunk_sizes or [w.B] * w.n_chunks
     diverged = False
@@ -99,6 +102,19 @@ def test_teacher_forced_stream_with_eviction_beside_attention(kw, monkeypatch):
         np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
         np.testing.assert_array_equal(host(V[m]), o.V[m].astype(np.float32))
         np.testing.assert_array_equal(S[m].cpu().numpy(), o.S[m])
+    layer.close()
+
+
+def test_teacher_forced_stream_with_pinned_query_prefix():
+    # Locret-Q: the first 48 tokens (the query, placed at the start) survive every eviction and keep
+    # positions 0..47, so every later chunk attends to them
+    w = synth.tiny(name="pinned", dtype="bf16", h=8, h_kv=2, d=128, N=2400, B=300, b=700, n_s=100, d_R=128)
+    layer, o, _ = _run_stream(w, teacher_forced=True, n_pin=48)
+    K, V, S, P = layer.cache_tensors()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+        assert P[m].cpu().numpy()[:48].tolist() == list(range(48))
+        np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
     layer.close()
 
 

@@ -100,3 +100,70 @@ def test_select_is_deterministic_and_reset_works():
     for a, b in zip(*runs):
         np.testing.assert_array_equal(a, b)
     layer.close()
+
+
+# ---- pinned prefix (Locret-Q): the first n_pin units survive every eviction ------------------------
+PIN_CASES = [
+    # name, workload overrides, n_pin, score kind
+    ("pin_f32", dict(dtype="f32", h=4, h_kv=2, d=64, N=4000, B=500, b=1000, n_s=64, rope=False), 100, "normal"),
+    ("pin_bf16_rope", dict(dtype="bf16", h=8, h_kv=4, d=128, N=9000, B=1000, b=3000, n_s=300), 777, "specials"),
+    ("pin_one", dict(dtype="bf16", h=2, h_kv=2, d=64, N=5000, B=1000, b=1500, n_s=10), 1, "ties"),
+    ("pin_fills_budget", dict(dtype="f32", h=2, h_kv=2, d=16, N=3000, B=300, b=512, n_s=12, rope=False), 500, "normal"),
+    ("pin_gt_first_chunk", dict(dtype="bf16", h=2, h_kv=1, d=96, N=6000, B=256, b=2000, n_s=700), 900, "ties"),
+    ("pin_keys_in_lds", dict(dtype="f32", h=1, h_kv=1, d=16, N=34000, B=2000, b=26000, n_s=100, rope=False), 333, "ties"),
+    ("pin_keys_in_global", dict(dtype="f32", h=1, h_kv=1, d=16, N=50000, B=2000, b=40000, n_s=7, rope=False), 64, "specials"),
+]
+
+
+@pytest.mark.parametrize("name,kw,n_pin,kind", PIN_CASES, ids=[c[0] for c in PIN_CASES])
+def test_evict_compact_with_pinned_prefix_bit_exact(name, kw, n_pin, kind):
+    w = synth.tiny(name=name, **kw)
+    layer, W1, W2 = make_layer(w)
+    o = make_oracle(w, W1, W2)
+    o.n_pin = n_pin
+    layer.set_pinned_prefix(n_pin)
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    for c in range(w.n_chunks):
+        lo, hi = w.chunk_range(c)
+        _, k, v = synth.tokens(w, lo, hi)
+        sc = _scores(rng, w.h_kv, hi - lo, kind)
+        if c == 0:
+            sc[:, :min(n_pin, hi - lo)] = -1e30        # on their merits the pinned units would go first
+        n_c = o.n_c
+        kept_ref = o.evict_compact(sc, k, v, w.n_s)
+        kept = layer.evict_compact(torch.from_numpy(sc).to(DEV), dev(k, w), dev(v, w), w.n_s)
+        n_keep = min(n_c + (hi - lo), w.b)
+        np.testing.assert_array_equal(kept.cpu().numpy()[:, :n_keep], kept_ref, err_msg=f"{name} chunk {c}")
+    K, V, S, P = layer.cache_tensors()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+        np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
+        np.testing.assert_array_equal(host(V[m]), o.V[m].astype(np.float32))
+        np.testing.assert_array_equal(S[m].cpu().numpy().view(np.uint32), o.S[m].view(np.uint32))
+        npp = min(n_pin, w.b - w.n_s)
+        assert P[m].cpu().numpy()[:npp].tolist() == list(range(npp))      # the stream's first tokens, in place
+    layer.close()
+
+
+def test_pinned_prefix_argument_errors_and_reset():
+    from paper_2410_01805_amd import binding as B
+    w = synth.tiny(name="pin_err", dtype="f32", h=2, h_kv=2, d=16, N=600, B=100, b=250, n_s=20, d_R=64, rope=False)
+    layer, _, _ = make_layer(w)
+    for bad in (-1, 251):
+        with pytest.raises(B.LocretError) as e:
+            layer.set_pinned_prefix(bad)
+        assert e.value.code == B.LOCRET_EINVAL
+    layer.set_pinned_prefix(240)
+    _, k, v = synth.tokens(w, 0, 100)
+    sc = torch.zeros(2, 100, device=DEV)
+    with pytest.raises(B.LocretError) as e:            # 240 pinned + 20 stabilizers > 250
+        layer.evict_compact(sc, dev(k, w), dev(v, w), 20)
+    assert e.value.code == B.LOCRET_EINVAL
+    assert layer.cache_len == 0
+    layer.evict_compact(sc, dev(k, w), dev(v, w), 10)
+    layer.reset()                                      # the setting survives a reset
+    with pytest.raises(B.LocretError):
+        layer.evict_compact(sc, dev(k, w), dev(v, w), 20)
+    layer.set_pinned_prefix(0)
+    layer.evict_compact(sc, dev(k, w), dev(v, w), 20)
+    layer.close()

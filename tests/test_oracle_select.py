@@ -150,6 +150,78 @@ def test_heads_evict_independently():
         assert o.P[m].tolist() == bf.closed_form_kept(scores[m], N, b, n_s)
 
 
+# ---- pinned prefix (Locret-Q: the query sits at the start of the sequence and is never evicted) -------
+PIN_HAND = [
+    # scores, budget, n_stab, n_pin, expected kept indices (written out by hand)
+    ([1, 5, 3, 2, 4], 3, 0, 1, [0, 1, 4]),                 # slot 0 forced although it scores lowest
+    ([1, 5, 3, 2, 4], 3, 1, 1, [0, 1, 4]),                 # first and last forced, best of the middle
+    ([1, 5, 3, 2, 4], 3, 1, 2, [0, 1, 4]),                 # prefix + stabilizer fill the budget
+    ([1, 2, 9, 8, 7, 3], 4, 1, 2, [0, 1, 2, 5]),
+    ([9, 9, 9], 8, 0, 2, [0, 1, 2]),                       # L < b keeps everything
+    ([1, 2], 5, 2, 3, [0, 1]),                             # stabilizers cover the list: nothing left to pin
+    ([4, 4, 4, 4, 4, 4], 4, 1, 1, [0, 1, 2, 5]),           # ties in the middle: lowest index
+    ([NAN, 1, 2, 3], 2, 0, 1, [0, 3]),                     # a pinned unit is kept whatever its score
+]
+
+
+@pytest.mark.parametrize("scores,b,ns,npin,want", PIN_HAND)
+def test_select_pinned_prefix_hand_cases(scores, b, ns, npin, want):
+    assert select_keep(np.array(scores, dtype=np.float32), b, ns, npin).tolist() == want
+
+
+def test_select_pinned_prefix_rejects_overfull_budget():
+    with pytest.raises(ValueError):
+        select_keep(np.arange(10, dtype=np.float32), 4, 2, 3)
+    assert select_keep(np.arange(10, dtype=np.float32), 5, 2, 3).tolist() == [0, 1, 2, 8, 9]
+
+
+def test_select_pinned_prefix_vs_sorted_bruteforce():
+    rng = np.random.default_rng(23)
+    for trial in range(300):
+        L = int(rng.integers(1, 80))
+        b = int(rng.integers(1, 90))
+        ns = int(rng.integers(0, b + 1))
+        npin = int(rng.integers(0, b - ns + 1))
+        s = rng.integers(-3, 4, size=L).astype(np.float32) * 0.5
+        for special in (np.nan, np.inf, -np.inf, -0.0):
+            if rng.random() < 0.3:
+                s[rng.integers(0, L)] = special
+        got = select_keep(s, b, ns, npin).tolist()
+        nsp = min(ns, L)
+        npp = min(npin, L - nsp)
+        n_keep = min(L, b)
+        cand = sorted(range(npp, L - nsp), key=lambda i: bf.rank_key(float(s[i]), i))
+        want = list(range(npp)) + sorted(cand[: n_keep - nsp - npp]) + list(range(L - nsp, L))
+        assert got == want, (trial, s, b, ns, npin)
+        assert select_keep(s, b, ns, 0).tolist() == select_keep(s, b, ns).tolist()
+
+
+@pytest.mark.parametrize("N,B,b,n_s,n_pin", [(200, 16, 40, 8, 5), (203, 16, 40, 24, 16), (150, 7, 21, 0, 21),
+                                            (120, 32, 33, 3, 30), (90, 10, 25, 5, 1)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_cache_loop_with_pinned_prefix_matches_closed_form_and_simulation(N, B, b, n_s, n_pin, ties):
+    rng = np.random.default_rng(N + 13 * n_pin)
+    scores = rng.standard_normal(N).astype(np.float32)
+    scores[:n_pin] = -50.0                     # the pinned tokens would be the first to go on their merits
+    if ties:
+        scores = np.round(scores * 2) / 2
+    o = LocretLayerOracle(1, 1, 1, b, np.zeros((3, 1)), np.zeros((1, 1)), n_pin=n_pin)
+    bounds, hist = [], []
+    for lo in range(0, N, B):
+        hi = min(N, lo + B)
+        kv = np.arange(lo, hi, dtype=np.float64).reshape(hi - lo, 1, 1)
+        o.evict_compact(scores[None, lo:hi], kv, -kv, n_s)
+        bounds.append(hi)
+        hist.append(o.P[0].tolist())
+        np.testing.assert_array_equal(o.S[0], scores[o.P[0]])            # true scores stored, not a mask value
+    sim = bf.simulate_algorithm1(scores, bounds, b, [n_s] * len(bounds), n_pin)
+    for c, end in enumerate(bounds):
+        assert hist[c] == sim[c]
+        assert hist[c] == bf.closed_form_kept(scores, end, b, n_s, n_pin)
+        npp = min(n_pin, end - min(n_s, end))
+        assert hist[c][:npp] == list(range(npp))                          # the prefix stays at the front
+
+
 # ---- numbers the paper prints --------------------------------------------------------------------
 def _golden():
     path = os.path.join(os.path.dirname(__file__), "golden", "paper_bookkeeping.txt")
