@@ -347,17 +347,14 @@ static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const voi
 // attention_dma.hip; head_dim 128 only, other head dims fall through to "w8"); "dma4" its
 // 4-wavefront form; "w8" register-staged, 8 wavefronts per workgroup; "w4" 4 wavefronts, two
 // workgroups per CU; "qb2" 4 wavefronts with 64 queries each; "pipe" attention_pipe.hip.
-static int attn_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("LOCRET_ATTN_VARIANT");
-    v = 4;
-    if (e && !strcmp(e, "w8")) v = 0;
-    if (e && !strcmp(e, "dma4")) v = 5;
-    if (e && !strcmp(e, "w4")) v = 1;
-    if (e && !strcmp(e, "qb2")) v = 2;
-    if (e && !strcmp(e, "pipe")) v = 3;
-  }
+static int attn_variant() {      // read on every launch (cheap), so a process can compare variants
+  const char* e = getenv("LOCRET_ATTN_VARIANT");
+  int v = 4;
+  if (e && !strcmp(e, "w8")) v = 0;
+  if (e && !strcmp(e, "dma4")) v = 5;
+  if (e && !strcmp(e, "w4")) v = 1;
+  if (e && !strcmp(e, "qb2")) v = 2;
+  if (e && !strcmp(e, "pipe")) v = 3;
   return v;
 }
 

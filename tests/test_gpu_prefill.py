@@ -118,6 +118,26 @@ def test_teacher_forced_stream_with_pinned_query_prefix():
     layer.close()
 
 
+@pytest.mark.parametrize("variant", ["dma4", "w8", "w4", "qb2", "pipe"])
+@pytest.mark.parametrize("kw", [SMALL[4], SMALL[7]], ids=["bf16_llama_like", "bf16_ns_gt_B"])
+def test_alternative_attention_kernels(kw, variant, monkeypatch):
+    # LOCRET_ATTN_VARIANT selects other forms of the head_dim-128 attention kernel (register-staged,
+    # 4-wavefront, 64 queries per wavefront, half-tile pipeline); each must meet the same bar
+    monkeypatch.setenv("LOCRET_ATTN_VARIANT", variant)
+    w = synth.tiny(**kw)
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    layer.close()
+
+
+def test_plain_kernels_on_bf16_storage(monkeypatch):
+    # LOCRET_FORCE_SIMPLE=1 (read when the context is created): the fp32 VALU attention and retaining
+    # head also serve bf16 tensors
+    monkeypatch.setenv("LOCRET_FORCE_SIMPLE", "1")
+    w = synth.tiny(**SMALL[4])
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    layer.close()
+
+
 def test_ragged_chunks_and_algorithm1_last_chunk():
     w = synth.tiny(name="ragged", dtype="bf16", h=8, h_kv=2, d=128, N=1500, B=400, b=500, n_s=60, d_R=128)
     layer, o, _ = _run_stream(w, chunk_sizes=[1, 400, 33, 64, 65, 127, 400, 10, 400], last_chunk_unmasked=True)
