@@ -2,9 +2,16 @@
 // staged global -> LDS directly (buffer_load ... lds, 16 bytes per lane): no staging registers,
 // no LDS stores, no register transposes, and a ring of tiles deep enough to cover memory latency.
 //
-// Arithmetic is that of attention_bf16.hip: S^T = K Q^T and O^T += V^T P^T with
-// v_mfma_f32_32x32x16_bf16, online softmax in fp32 with lazy rescale, one wavefront = 32 queries
-// of one head, all wavefronts of a workgroup on one KV head.
+// Products as in attention_bf16.hip: S^T = K Q^T and O^T += V^T P^T with v_mfma_f32_32x32x16_bf16,
+// one wavefront = 32 queries of one head, all wavefronts of a workgroup on one KV head.
+//
+// Softmax with as little vector-ALU work as the arithmetic allows (the matrix pipe and the vector
+// ALU overlap only partly, so every VALU instruction per tile costs time): the queries are scaled
+// by scale * log2(e) when they are loaded, and the S chain starts from an accumulator that holds
+// -(running max), so the MFMA result is already the exponent; per tile the VALU then only does the
+// 32 exp2, 16 bf16 packs and 16 two-way dot products that sum the packed probabilities.  The
+// running max moves only on the first tile and when a lane's probability sum reaches 2^8: no row
+// max is formed otherwise.
 //
 // LDS layout of one ring stage (32 KB): K tile then V tile, both [64 keys][128 dims] row-major,
 // 256 bytes per row, no padding.  A direct load writes lane L's 16 bytes at base + 16 L, i.e. one
@@ -94,6 +101,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
     const bf16_t* qp = q + ((int64_t)my_t * h + j) * D + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
+    const float qscale = c_log2;                 // logits come out of the MFMA in log2 units
     if (tab != nullptr) {
       // un-rotated queries: rotate to position n_c + t here (pairs (i, i + D/2) sit in fragments ks
       // and ks + NKS/2 of the same lane), round to bf16 as the append kernel would have
@@ -105,13 +113,22 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
         for (int e = 0; e < 8; ++e) {
           const float2 cs = tp[ks * 16 + e];
           const float a = (float)qf[ks][e], b = (float)qf[ks + NKS / 2][e];
-          lo[e] = a * cs.x - b * cs.y;
-          up[e] = b * cs.x + a * cs.y;
+          lo[e] = (a * cs.x - b * cs.y) * qscale;
+          up[e] = (b * cs.x + a * cs.y) * qscale;
         }
         uint4 pl = make_uint4(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(lo[4], lo[5]), pack_bf16(lo[6], lo[7]));
         uint4 pu = make_uint4(pack_bf16(up[0], up[1]), pack_bf16(up[2], up[3]), pack_bf16(up[4], up[5]), pack_bf16(up[6], up[7]));
         qf[ks] = __builtin_bit_cast(bf16x8, pl);
         qf[ks + NKS / 2] = __builtin_bit_cast(bf16x8, pu);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (float)qf[ks][e] * qscale;
+        uint4 px = make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        qf[ks] = __builtin_bit_cast(bf16x8, px);
       }
     }
   }
@@ -120,7 +137,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
   for (int db = 0; db < NDB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = 0.f, l_run = 0.f;
+  // m_run is in log2 units and negm holds -m_run in all 16 registers: the first MFMA of every S
+  // chain takes it as its addend, so the accumulator ends as (logit - running max) and exp2 applies
+  // to it directly.  `fresh` (wave-uniform) is true until the first tile has set the max.
+  f32x16 negm;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+  bool fresh = true;
 
   // ---- direct loads: instruction i of a tile covers rows 4i .. 4i+3; wavefront w issues
   // ---- instructions w, w + NW, ... so (i & 3) is the same for all of them -------------------------
@@ -168,9 +192,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
     const unsigned char* sb = ring + stage * DM_STAGE_B;
     f32x16 sacc[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    for (int kb = 0; kb < 2; ++kb) sacc[kb] = negm;   // the S chain starts from -(running max)
     {
       bf16x8 kf[NKS][2];
 #pragma unroll
@@ -200,37 +222,62 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
           if (slot > limit) sacc[kb][r] = -INFINITY;
         }
     }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-    mx = max_across_halves(mx);
-    const float m_new = fmaxf(m_run, mx);       // finite from tile 0 on (slot 0 is visible to all)
-    if (__any((m_new - m_run) * c_log2 > RESCALE_LOG2)) {   // lazy rescale, see attention_bf16.hip
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    const float mc = m_run * c_log2;
-    float psum = 0.f;
     uint4 pb[4];
+    {
+      // The accumulator holds (logit - running max) in log2 units: exponentiate, pack to bf16, and sum
+      // the packed probabilities (as the V product will see them) two per instruction.
+      float ps;
+      auto exp_pack_sum = [&]() {
+        float ps0 = 0.f, ps1 = 0.f;
+        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
+        for (int kb = 0; kb < 2; ++kb) {
+          uint32_t w[8];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
-        psum += p[r];
+          for (int r = 0; r < 16; r += 2)
+            w[r >> 1] = pack_bf16(__builtin_amdgcn_exp2f(sacc[kb][r]), __builtin_amdgcn_exp2f(sacc[kb][r + 1]));
+#pragma unroll
+          for (int i = 0; i < 8; i += 2) {
+            ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i]), ones, ps0, false);
+            ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i + 1]), ones, ps1, false);
+          }
+          pb[kb * 2 + 0] = make_uint4(w[0], w[1], w[2], w[3]);
+          pb[kb * 2 + 1] = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+        ps = ps0 + ps1;
+      };
+      exp_pack_sum();
+      // The running max is only moved when it has to be: on the first tile, and when some lane's sum
+      // over its 32 keys reaches 2^RESCALE_LOG2 (any probability that large, an overflow included,
+      // shows there).  No row max is formed on the common path.  Rare path: take the row max, raise
+      // the running max by it, scale sum and accumulator, refresh negm, correct this tile's logits
+      // (formed against the old max) and redo its probabilities.
+      if (fresh || __any(!(ps < 256.f))) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+        mx = max_across_halves(mx);
+        const float delta = fresh ? mx : fmaxf(mx, 0.f);
+        const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet when fresh
+        m_run += delta;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negm[r] = -m_run;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kb][r] -= delta;
+        fresh = false;
+        exp_pack_sum();
       }
-      pb[kb * 2 + 0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-      pb[kb * 2 + 1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]), pack_bf16(p[14], p[15]));
+      l_run += ps;
     }
-    l_run += psum;
     {
       // V^T fragments: two transposing 8-byte reads each (keys +0..3 and +8..11 of the 16-key chunk)
       bf16x8 vf[4][NDB];
