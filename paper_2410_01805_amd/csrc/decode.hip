@@ -167,7 +167,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
 // A separate launch on purpose: letting the last workgroup of a head merge behind a device-scope
 // fence was measured 3x slower than both kernels together (every workgroup then pays for making its
 // partials visible across the eight L2s), while a kernel boundary does that once.
-constexpr int DEC_MERGE_THREADS = 256;
+constexpr int DEC_MERGE_THREADS = 1024;
 template <typename T>
 __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const float* __restrict__ part, int n_splits,
                                                                          int d, T* __restrict__ out) {
@@ -197,12 +197,18 @@ __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const f
   const float inv = 1.f / l;
   // thread (e, r): element e, splits r, r + R, ...; the R partial sums of an element meet in LDS
   __shared__ float acc_s[DEC_MERGE_THREADS];
-  const int R = DEC_MERGE_THREADS / 128;       // d <= 128
+  constexpr int R = DEC_MERGE_THREADS / 128;   // d <= 128
   const int e = tid % 128, r = tid / 128;
-  float a = 0.f;
-  if (e < d)
-    for (int s = r; s < n_splits; s += R) a = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a);
-  acc_s[tid] = a;
+  float a0 = 0.f, a1 = 0.f;
+  if (e < d) {
+    int s = r;
+    for (; s + R < n_splits; s += 2 * R) {     // two independent loads in flight
+      a0 = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a0);
+      a1 = fmaf(__builtin_amdgcn_exp2f(p[(s + R) * pw + d] - M), p[(s + R) * pw + e], a1);
+    }
+    if (s < n_splits) a0 = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a0);
+  }
+  acc_s[tid] = a0 + a1;
   __syncthreads();
   if (tid < d) {
     float t = 0.f;
@@ -212,7 +218,6 @@ __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const f
   }
 }
 
-// keys per workgroup; LOCRET_DEC_KEYS (a multiple of 64, read once) overrides it for experiments
 int decode_keys_per_split() {
   static int v = 0;
   if (v == 0) {
