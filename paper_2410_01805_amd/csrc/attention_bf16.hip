@@ -32,7 +32,7 @@
 namespace locret {
 
 template <int D, int QB, int NW, int WPE>
-__global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
+__global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c, float c_log2,
                                                              int hpw, int n_hgroups, int n_ttiles) {
@@ -86,6 +86,36 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
     const bf16_t* qp = q + ((int64_t)t * h + j) * D + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + ks * 16);
+    // Queries are scaled by scale * log2(e) here, so logits leave the MFMA in log2 units; with `tab`
+    // they arrive un-rotated and are rotated to position n_c + t first (pairs (i, i + D/2) sit in
+    // fragments ks and ks + NKS/2 of the same lane).  One rounding to bf16 either way.
+    if (tab != nullptr) {
+      const float2* tp = tab + (int64_t)(n_c + t) * (D / 2) + hi * 8;
+#pragma unroll
+      for (int ks = 0; ks < NKS / 2; ++ks) {
+        float lo[8], up[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 cs = tp[ks * 16 + e];
+          const float a = (float)qf[qb][ks][e], b = (float)qf[qb][ks + NKS / 2][e];
+          lo[e] = (a * cs.x - b * cs.y) * c_log2;
+          up[e] = (b * cs.x + a * cs.y) * c_log2;
+        }
+        uint4 pl = make_uint4(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(lo[4], lo[5]), pack_bf16(lo[6], lo[7]));
+        uint4 pu = make_uint4(pack_bf16(up[0], up[1]), pack_bf16(up[2], up[3]), pack_bf16(up[4], up[5]), pack_bf16(up[6], up[7]));
+        qf[qb][ks] = __builtin_bit_cast(bf16x8, pl);
+        qf[qb][ks + NKS / 2] = __builtin_bit_cast(bf16x8, pu);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (float)qf[qb][ks][e] * c_log2;
+        uint4 px = make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        qf[qb][ks] = __builtin_bit_cast(bf16x8, px);
+      }
+    }
   }
 
   f32x16 oacc[NDB][QB];
@@ -95,9 +125,19 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
+  // Softmax state per query block: running max m_run (log2 units), running sum l_run, and negm = -m_run
+  // in all 16 registers: every S chain starts from it, so the MFMA result is (logit - running max) and
+  // exp2 applies to it directly.  `fresh` (wave-uniform) is true until the first tile has set the max.
   float m_run[QB], l_run[QB];
+  f32x16 negm[QB];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = 0.f;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[qb][r] = 0.f;
+  }
+  bool fresh = true;
 
   // ---- staging: a K tile is one contiguous block of KT*KCH 16-byte chunks, 256 threads take
   // ---- chunks st + 256 i; a V tile is cut into 4-key x 8-dim blocks, one per thread of 256.
@@ -191,9 +231,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+      for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = negm[qb];
     {
       bf16x8 kf[NKS][2];
 #pragma unroll
@@ -229,42 +267,58 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
             if (slot > limit) sacc[kb][qb][r] = -INFINITY;
           }
       }
-      float mx = -INFINITY;
+      // exponentiate, pack to bf16, and sum the packed probabilities two per instruction
+      float ps;
+      auto exp_pack_sum = [&]() {
+        float ps0 = 0.f, ps1 = 0.f;
+        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb) {
+          uint32_t w[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
-      mx = max_across_halves(mx);
-      // Lazy rescale: the running max is raised (and O, l rescaled) only when some query of the
-      // wavefront would otherwise see a probability above 2^RESCALE_LOG2; until then the stale
-      // max keeps every exponent bounded and the rescale pass over the O registers is skipped.
-      const float m_new = fmaxf(m_run[qb], mx);          // finite from tile 0 on (slot 0 is visible to all)
-      if (__any((m_new - m_run[qb]) * c_log2 > RESCALE_LOG2)) {
-        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c_log2);
-        m_run[qb] = m_new;
+          for (int r = 0; r < 16; r += 2)
+            w[r >> 1] = pack_bf16(__builtin_amdgcn_exp2f(sacc[kb][qb][r]), __builtin_amdgcn_exp2f(sacc[kb][qb][r + 1]));
+#pragma unroll
+          for (int i = 0; i < 8; i += 2) {
+            ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i]), ones, ps0, false);
+            ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i + 1]), ones, ps1, false);
+          }
+          pb[qb][kb * 2 + 0] = make_uint4(w[0], w[1], w[2], w[3]);
+          pb[qb][kb * 2 + 1] = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+        ps = ps0 + ps1;
+      };
+      exp_pack_sum();
+      // The running max moves only on the first tile and when some lane's sum over its 32 keys reaches
+      // 2^RESCALE_LOG2 (any probability that large, an overflow included, shows there): then take the
+      // row max, raise the running max by it, scale sum and accumulator, refresh negm, correct this
+      // tile's logits (formed against the old max) and redo its probabilities.
+      if (fresh || __any(!(ps < 256.f))) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][qb][r]);
+        mx = max_across_halves(mx);
+        const float delta = fresh ? mx : fmaxf(mx, 0.f);
+        const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet when fresh
+        m_run[qb] += delta;
         l_run[qb] *= alpha;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-      }
-      const float mc = m_run[qb] * c_log2;
-      float psum = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float p[16];
+        for (int r = 0; r < 16; ++r) negm[qb][r] = -m_run[qb];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][r], c_log2, -mc));
-          psum += p[r];
-        }
-        pb[qb][kb * 2 + 0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
-                                        pack_bf16(p[6], p[7]));
-        pb[qb][kb * 2 + 1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
-                                        pack_bf16(p[14], p[15]));
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kb][qb][r] -= delta;
+        exp_pack_sum();
       }
-      l_run[qb] += psum;
+      l_run[qb] += ps;
     }
+    fresh = false;
     {
       bf16x8 vf[4][NDB];
 #pragma unroll
@@ -329,8 +383,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
 }
 
 template <int D, int QB, int NW, int WPE>
-static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                        float scale, hipStream_t st) {
+static void attn_launch(const Dims& Dm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T,
+                        int n_c, float scale, hipStream_t st) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
   const int wph = NW / hpw;
@@ -338,7 +392,7 @@ static void attn_launch(const Dims& Dm, const void* q, const void* Kx, const voi
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, (const bf16_t*)q,
+  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, (const bf16_t*)q, tab,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
                      n_hgroups, n_ttiles);
 }
@@ -362,18 +416,19 @@ static bool dma_applies(const Dims& Dm) {
   return attn_variant() >= 4 && Dm.d == 128 && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
 }
 
-bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && dma_applies(Dm); }
+// every kernel here except the half-tile pipeline takes un-rotated queries and rotates them itself
+bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && (attn_variant() != 3 || dma_applies(Dm)); }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab) {
   const int v = attn_variant();
   if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
-#define LOCRET_CASE(DD)                                                               \
-  case DD:                                                                            \
-    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);       \
-    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, q, Kx, V, out, T, n_c, scale, st);  \
-    else attn_launch<DD, 1, 8, 2>(Dm, q, Kx, V, out, T, n_c, scale, st);              \
+#define LOCRET_CASE(DD)                                                                           \
+  case DD:                                                                                        \
+    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);        \
+    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);   \
+    else attn_launch<DD, 1, 8, 2>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);               \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)
