@@ -151,8 +151,10 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
     // a bare barrier: __syncthreads() would first drain every load in flight (they count as
     // memory writes), which is exactly what the ring is there to avoid
     asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    issue(s + RT_STAGES - 1, (buf + RT_STAGES - 1) % RT_STAGES);
+    // compute first: the MFMAs of this stage are queued before the wavefront spends its issue slots on
+    // the direct loads of stage s + 3 (they go into the slot every wavefront left before this barrier)
     compute(buf);
+    issue(s + RT_STAGES - 1, (buf + RT_STAGES - 1) % RT_STAGES);
   };
 
   issue(0, 0);
