@@ -12,8 +12,9 @@
 // workgroup of four wavefronts per CU it is this depth, not occupancy, that hides memory latency.
 // Such a load writes lane L's 16 bytes at LDS base + 16 L, so an instruction fills 8 rows of 128
 // bytes back to back; bank conflicts are avoided by permuting WHICH 16-byte chunk a lane fetches:
-// position c' of row r holds chunk c' ^ (r & 7), and a fragment read of logical chunk c goes to
-// position c ^ (r & 7).  Rows past the chunk (t >= T) fall outside the buffer descriptor and arrive
+// position c' of row r holds chunk c' ^ ((r >> 1) & 7), and a fragment read of logical chunk c goes to
+// position c ^ ((r >> 1) & 7): rows are 128 bytes, so even and odd rows already sit in different halves
+// of the 64 banks, and the 8 even (or odd) rows among 16 consecutive ones must take 8 different positions.  Rows past the chunk (t >= T) fall outside the buffer descriptor and arrive
 // as zeros.
 //
 // SiLU and the product with W2 run on the accumulators; the workgroup writes its partial score
@@ -71,8 +72,11 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 
   // ---- loads: wavefront w fills rows w*32 .. w*32+31 of both tiles, 8 rows per instruction -------
   const int l_row = lane >> 3;                           // row inside the instruction's 8 rows
-  const int l_csw = ((lane & 7) ^ l_row) * 16;           // byte offset of the chunk this lane fetches
-  const int a_vo = (wave * 32 + l_row) * (K * 2) + l_csw;   // + ii * 8 rows
+  // byte offset of the chunk this lane fetches: row = 8 * instruction + l_row, so (row >> 1) & 7 is
+  // (l_row >> 1) for even instructions and (l_row >> 1) ^ 4 for odd ones (ii & 1 below)
+  const int l_csw0 = ((lane & 7) ^ (l_row >> 1)) * 16;
+  const int l_csw1 = ((lane & 7) ^ (l_row >> 1) ^ 4) * 16;
+  const int a_vo = (wave * 32 + l_row) * (K * 2);        // + ii * 8 rows + chunk offset
   const int b_row = wave * 32 + l_row;                   // + ii * 8
   const int n_stages = K / RT_K;
   const int q_stages = hd / RT_K, k_stages = kvd / RT_K;
@@ -88,7 +92,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int ii = 0; ii < 4; ++ii)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            ar, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + (wave * 4 + ii) * 1024), 16, a_vo + ii * 8 * (K * 2), 0, 0, 0);
+            ar, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + (wave * 4 + ii) * 1024), 16, a_vo + ii * 8 * (K * 2) + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
     }
     {
       const bf16_t* src;
@@ -104,15 +108,15 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
       for (int ii = 0; ii < 4; ++ii)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (wave * 4 + ii) * 1024), 16,
-            (b_row + ii * 8) * rowb + l_csw, 0, 0, 0);
+            (b_row + ii * 8) * rowb + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
     }
   };
 
-  // ---- fragment reads: row (wave part + n32), logical chunk 2 ks + hi at position chunk ^ (row & 7)
+  // ---- fragment reads: row (wave part + n32), logical chunk 2 ks + hi at position chunk ^ ((row >> 1) & 7)
   int a_rd[4], b_rd[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    const int pos = ((2 * ks + hi) ^ (n32 & 7)) * 16;
+    const int pos = ((2 * ks + hi) ^ ((n32 >> 1) & 7)) * 16;
     a_rd[ks] = (wm * 64 + n32) * 128 + pos;
     b_rd[ks] = RT_TILE_B + (wn * 64 + n32) * 128 + pos;
   }
