@@ -18,6 +18,11 @@
 // exchange with lane^32, and P^T leaves the accumulator already in B-operand order provided the
 // V^T tile stores its keys in the matching order (each group of 16 keys as 0-3, 8-11, 4-7, 12-15).
 //
+// Softmax as in attention_dma.hip: queries pre-scaled by scale * log2(e) (and rotated here when the
+// rotary table is passed), S chains started from -(running max), exp2 / bf16 pack / two-way dot
+// products per tile, the running max moved only on the first tile and when a lane's probability
+// sum reaches 2^8.
+//
 // K tile in LDS: [64 keys][D + 8]; V^T tile in LDS: [D][64 + 8], transposed on the way in by 4x8
 // register blocks.  The 16-byte row pad makes the stride an odd number of 16-byte chunks, so the
 // 16-byte row reads of consecutive lanes and the 8-byte transposing writes both spread over all
@@ -32,8 +37,9 @@
 namespace locret {
 
 template <int D, int QB, int NW, int WPE>
-__global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
-                                                             const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab,
+                                                             const bf16_t* __restrict__ Kx, const bf16_t* __restrict__ V,
+                                                             bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c, float c_log2,
                                                              int hpw, int n_hgroups, int n_ttiles) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
