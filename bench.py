@@ -115,7 +115,11 @@ def main():
         del x, y
 
     # ---- timed region ---------------------------------------------------------------------------------
+    # Inside it only the dominant kernel (attention) is timed, through its own dispatch, which puts no
+    # extra packets into the stream; timing every stage with events between the kernels costs about
+    # 3 % of a step, so the other stages are timed in a second pass over the same steps below.
     B.locret_reset(layer.ctx)
+    B.locret_profile_mode(layer.ctx, 1)
     B.locret_profile_enable(layer.ctx, K)
     plan = []           # (n_c before the call, T) per timed step, for the work model
     n_c = 0
@@ -135,8 +139,20 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     total_ms = e0.elapsed_time(e1)
+    attn_ms, n_attn = B.locret_profile_read(layer.ctx)
+    B.locret_profile_enable(layer.ctx, 0)
+
+    # ---- second pass over the same steps, every stage timed (not part of `value`) ------------------------
+    B.locret_profile_mode(layer.ctx, 0)
+    B.locret_profile_enable(layer.ctx, K)
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
     stage_ms, n_prof = B.locret_profile_read(layer.ctx)
     B.locret_profile_enable(layer.ctx, 0)
+    stage_ms = list(stage_ms)
+    if n_attn == K:                      # the live figure of the timed region (else: a kernel that is timed with events)
+        stage_ms[1] = attn_ms[1]
 
     fl_attn = sum(attention_flops(w, nc, T) for nc, T in plan)
     fl_score = sum(score_flops(w, T) for nc, T in plan)
@@ -150,6 +166,7 @@ def main():
         "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_ATTENTION_TRAFFIC_BYTES.get(w.name),
         "algorithmic_bytes_steady": (2 * w.h_kv * (w.b + w.B) + 2 * w.B * w.h) * w.d * (2 if w.dtype == "bf16" else 4),
         "avg_launch_ms": round(ms["attention"] / max(1, n_prof), 4),
+        "timed_by": "kernel dispatch timestamps, inside the timed region" if n_attn == K else "events around the launch, second pass",
         "flops_per_launch_steady": attention_flops(w, w.b, w.B),
     }
     mlp_tflops = fl_score / (ms["retaining_head"] * 1e-3) / 1e12

@@ -161,8 +161,15 @@ int locret_cache_view(const locret_ctx* ctx, const void** K, const void** V, con
  * 0 append+rotate, 1 attention, 2 retaining head, 3 select, 4 compact).  locret_profile_read waits
  * for the recorded events, writes the summed milliseconds per stage to stage_ms (HOST, 5 doubles)
  * and the number of calls covered to *n_calls (HOST), and starts a new window.  Calls beyond
- * max_calls in one window are not recorded. */
+ * max_calls in one window are not recorded.
+ * An event between two kernels costs a few microseconds of idle stream, so timing every stage
+ * slows a step by about 3 %.  locret_profile_mode(ctx, 1) times the attention kernel only, through
+ * its own dispatch (no extra packets in the stream: the step runs at full speed); the other entries
+ * of stage_ms are then 0, and if the attention kernel in use cannot be timed that way *n_calls is 0.
+ * Mode 0 (default) times every stage.  The mode can be changed while no recorded call is unread
+ * (LOCRET_ESTATE otherwise). */
 #define LOCRET_PROF_STAGES 5
+int locret_profile_mode(locret_ctx* ctx, int32_t mode);
 int locret_profile_enable(locret_ctx* ctx, int32_t max_calls);
 int locret_profile_read(locret_ctx* ctx, double* stage_ms, int32_t* n_calls);
 

@@ -23,7 +23,7 @@ LOCRET_F32, LOCRET_BF16 = 0, 1
 EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_set_pinned_prefix", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
-    "locret_destroy", "locret_strerror", "locret_profile_enable", "locret_profile_read",
+    "locret_destroy", "locret_strerror", "locret_profile_mode", "locret_profile_enable", "locret_profile_read",
 ]
 LOCRET_PROF_STAGES = 5
 PROF_STAGE_NAMES = ("append", "attention", "retaining_head", "select", "compact")
@@ -59,6 +59,8 @@ def _load() -> C.CDLL:
     lib.locret_decode_step.argtypes = [vp, vp, vp, vp, i32, vp, f32p, vp]
     lib.locret_evict_compact.restype = C.c_int
     lib.locret_evict_compact.argtypes = [vp, f32p, vp, vp, i32, i32, i32p, vp]
+    lib.locret_profile_mode.restype = C.c_int
+    lib.locret_profile_mode.argtypes = [vp, i32]
     lib.locret_set_pinned_prefix.restype = C.c_int
     lib.locret_set_pinned_prefix.argtypes = [vp, i32]
     lib.locret_cache_len.restype = C.c_int32
@@ -143,6 +145,10 @@ def locret_prefill_chunk(ctx, q, k, v, T, n_stab, evict, scores_in, attn_out, sc
     _check(lib.locret_prefill_chunk(ctx, _ptr(q), _ptr(k), _ptr(v), T, n_stab, evict, _ptr(scores_in),
                                     _ptr(attn_out), _ptr(scores_out), _ptr(kept_idx_out), _stream(stream)),
            "locret_prefill_chunk")
+
+
+def locret_profile_mode(ctx, mode: int) -> None:
+    _check(lib.locret_profile_mode(ctx, mode), "locret_profile_mode")
 
 
 def locret_set_pinned_prefix(ctx, n_pin: int) -> None:

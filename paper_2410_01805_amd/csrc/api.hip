@@ -104,8 +104,10 @@ struct locret_ctx {
   int overlap;
   std::vector<hipEvent_t> ev;   // profiling: a (begin, end) pair per stage per recorded call
   int prof_max, prof_calls;
+  int prof_mode;    // 0: every stage (event packets between the kernels), 1: attention only (no extra packets)
+  hipEvent_t prof_event(int stage, int end) { return ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end]; }
   void mark(int stage, int end, hipStream_t st) {
-    if (prof_calls < prof_max) (void)hipEventRecord(ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end], st);
+    if (prof_calls < prof_max && prof_mode == 0) (void)hipEventRecord(ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end], st);
   }
   CacheBuf buf(int i) const {
     CacheBuf b;
@@ -138,7 +140,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   locret_ctx* c = new (std::nothrow) locret_ctx();
   if (!c) return LOCRET_ENOMEM;
   c->cur = 0; c->n_c = 0; c->seen = 0; c->have_weights = 0; c->prof_max = 0; c->prof_calls = 0;
-  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0; c->n_pin = 0;
+  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0; c->n_pin = 0; c->prof_mode = 0;
   c->cfg = *cfg;
   fill_dims(cfg, &c->D);
   make_layout(cfg, c->D, &c->L);
@@ -264,6 +266,15 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const int n_c = c->n_c;
   const int L = n_c + T;
   auto attention = [&]() {
+    // when profiling, the matrix-core kernels are timed through their own dispatch
+    const bool prof = c->prof_calls < c->prof_max;
+    if (c->mfma_attn && prof && attention_bf16_attaches_timer(D)) {
+      LaunchTimer tm;
+      tm.start = c->prof_event(1, 0);
+      tm.stop = c->prof_event(1, 1);
+      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm);
+      return;
+    }
     c->mark(1, 0, st);
     if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr);
     else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st);
@@ -383,13 +394,27 @@ int locret_profile_enable(locret_ctx* c, int32_t max_calls) {
   return LOCRET_OK;
 }
 
+int locret_profile_mode(locret_ctx* c, int32_t mode) {
+  if (!c || (mode != 0 && mode != 1)) return LOCRET_EINVAL;
+  if (c->prof_calls != 0) return LOCRET_ESTATE;       // read or re-arm first
+  c->prof_mode = mode;
+  return LOCRET_OK;
+}
+
 int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
   if (!c || !stage_ms || !n_calls) return LOCRET_EINVAL;
   for (int s = 0; s < LOCRET_PROF_STAGES; ++s) stage_ms[s] = 0.0;
   *n_calls = c->prof_calls;
+  const bool attn_only = c->prof_mode == 1;
+  if (attn_only && !(c->mfma_attn && attention_bf16_attaches_timer(c->D))) {   // nothing was time-stamped
+    c->prof_calls = 0;
+    *n_calls = 0;
+    return LOCRET_OK;
+  }
   for (int i = 0; i < c->prof_calls; ++i) {
     hipEvent_t* e = &c->ev[(size_t)i * LOCRET_PROF_STAGES * 2];
     for (int s = 0; s < LOCRET_PROF_STAGES; ++s) {
+      if (attn_only && s != 1) continue;
       float ms = 0.f;
       if (hipEventSynchronize(e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;
       if (hipEventElapsedTime(&ms, e[2 * s], e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;

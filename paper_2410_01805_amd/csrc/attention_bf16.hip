@@ -29,6 +29,7 @@
 // banks, and every LDS address is "per-thread base + compile-time offset".  Tiles are double
 // buffered through registers (one barrier per 64 keys); the tile loop is unrolled by two so the
 // buffer index is a compile-time constant, and only the last tile pays for bounds checks.
+#include <hip/hip_ext.h>
 #include <string.h>
 
 #include "attn_common.h"
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
 }
 
 template <int D, int QB, int NW, int WPE>
-static void attn_launch(const Dims& Dm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T,
+static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T,
                         int n_c, float scale, hipStream_t st) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
@@ -398,7 +399,8 @@ static void attn_launch(const Dims& Dm, const void* q, const float2* tab, const 
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, (const bf16_t*)q, tab,
+  hipExtLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop,
+                        0, (const bf16_t*)q, tab,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
                      n_hgroups, n_ttiles);
 }
@@ -422,19 +424,25 @@ static bool dma_applies(const Dims& Dm) {
   return attn_variant() >= 4 && Dm.d == 128 && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
 }
 
+// true when launch_attention_bf16 hands its LaunchTimer to the kernel's own dispatch (every kernel here
+// except the half-tile pipeline, which ignores it)
+bool attention_bf16_attaches_timer(const Dims& Dm) {
+  return (attn_variant() != 3 || dma_applies(Dm)) && (Dm.d == 64 || Dm.d == 96 || Dm.d == 128);
+}
+
 // every kernel here except the half-tile pipeline takes un-rotated queries and rotates them itself
 bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && (attn_variant() != 3 || dma_applies(Dm)); }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                           float scale, hipStream_t st, const float2* q_rot_tab) {
+                           float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm) {
   const int v = attn_variant();
-  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
+  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
 #define LOCRET_CASE(DD)                                                                           \
   case DD:                                                                                        \
-    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);        \
-    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);   \
-    else attn_launch<DD, 1, 8, 2>(Dm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);               \
+    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);        \
+    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);   \
+    else attn_launch<DD, 1, 8, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);               \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)

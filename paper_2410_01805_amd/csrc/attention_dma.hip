@@ -33,6 +33,8 @@
 // right after it and stay in flight across the compute that follows), starts the loads into the
 // stages just vacated, and computes.  Tiles past the staged slots are fetched through an empty
 // buffer descriptor: they arrive as zeros without touching memory.
+#include <hip/hip_ext.h>
+
 #include "attn_common.h"
 #include "kernels.h"
 
@@ -361,7 +363,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
 }
 
 template <int NW, int NSTAGE>
-static void dma_launch(const Dims& Dm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T, int n_c,
+static void dma_launch(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T, int n_c,
                        float scale, hipStream_t st) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
@@ -370,19 +372,19 @@ static void dma_launch(const Dims& Dm, const void* q, const float2* tab, const v
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((attn_dma_kernel<NW, NSTAGE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st,
+  hipExtLaunchKernelGGL((attn_dma_kernel<NW, NSTAGE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
                      (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
                      c_log2, hpw, n_hgroups, n_ttiles);
 }
 
 // `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
 // variant 0: 8 wavefronts, 4-stage ring (one workgroup per CU); 1: 4 wavefronts, 2-stage ring (two per CU)
-bool launch_attention_bf16_dma(const Dims& Dm, int variant, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
+bool launch_attention_bf16_dma(const Dims& Dm, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                                int T, int n_c, float scale, hipStream_t st) {
   if (Dm.d != DM_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
-  if (variant == 1) dma_launch<4, 2>(Dm, q, tab, Kx, V, out, T, n_c, scale, st);
-  else dma_launch<8, 4>(Dm, q, tab, Kx, V, out, T, n_c, scale, st);
+  if (variant == 1) dma_launch<4, 2>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st);
+  else dma_launch<8, 4>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st);
   return true;
 }
 

@@ -6,6 +6,14 @@
 
 namespace locret {
 
+// Optional pair of events a launcher attaches to its dominant kernel's own dispatch
+// (hipExtLaunchKernelGGL): the kernel's begin and end are time-stamped without separate event
+// packets in the stream, which each cost a few microseconds of bubble.  Null = plain launch.
+struct LaunchTimer {
+  hipEvent_t start = nullptr;
+  hipEvent_t stop = nullptr;
+};
+
 struct Dims {
   int h;        // query heads
   int h_kv;     // KV heads
@@ -51,14 +59,17 @@ bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, co
                                 int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel with K/V staged global->LDS directly (d = 128 only); false if the shape is not
 // covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
-bool launch_attention_bf16_dma(const Dims& D, int variant, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
+bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                                int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
-                           int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr);
+                           int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr,
+                           LaunchTimer tm = LaunchTimer());
 // True when launch_attention_bf16 takes un-rotated queries plus the rotary table for these
 // dimensions (the kernel rotates them itself); otherwise it expects rotated queries.
 bool attention_bf16_rotates_q(const Dims& D);
+// True when launch_attention_bf16 attaches the LaunchTimer's events to the attention kernel's dispatch.
+bool attention_bf16_attaches_timer(const Dims& D);
 
 // Decode step (Eq. 1 with B = 1): one query row per head (rotated if rope) over slots [0, n_keys).
 // `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.

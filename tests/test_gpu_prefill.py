@@ -223,3 +223,30 @@ def test_state_and_argument_errors_on_device():
     assert e.value.code == B.LOCRET_EALIGN
     assert layer.cache_len == 0                   # nothing was changed by the failed calls
     layer.close()
+
+
+def test_profile_modes():
+    from paper_2410_01805_amd import binding as B
+    w = synth.tiny(name="prof", dtype="bf16", h=8, h_kv=2, d=128, N=1200, B=300, b=700, n_s=50, d_R=128)
+    layer, _, _ = make_layer(w)
+    chunks = [tuple(dev(x, w) for x in synth.chunk(w, c)) for c in range(4)]
+    for mode in (0, 1):
+        layer.reset()
+        B.locret_profile_mode(layer.ctx, mode)
+        B.locret_profile_enable(layer.ctx, 3)            # the 4th call is not recorded
+        for q, k, v in chunks:
+            layer.prefill_chunk(q, k, v, w.n_s)
+        with pytest.raises(B.LocretError) as e:          # recorded calls are still unread
+            B.locret_profile_mode(layer.ctx, 1 - mode)
+        assert e.value.code == B.LOCRET_ESTATE
+        ms, n = B.locret_profile_read(layer.ctx)
+        assert n == 3 and 0.0 < ms[1] < 50.0             # attention was timed
+        if mode == 0:
+            assert all(x > 0.0 for x in ms)              # every stage (compaction ran from the third chunk on)
+        else:
+            assert ms[0] == ms[2] == ms[3] == ms[4] == 0.0
+        B.locret_profile_enable(layer.ctx, 0)
+    with pytest.raises(B.LocretError):
+        B.locret_profile_mode(layer.ctx, 2)
+    layer.close()
+
