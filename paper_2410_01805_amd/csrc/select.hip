@@ -300,18 +300,20 @@ __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __
   }
 }
 
-static int g_lds_limit = -1;   // bytes of dynamic LDS the in-LDS variant may use
+// bytes of dynamic LDS the in-LDS variant may use: asked for once (thread-safe static initialisation)
+static int lds_limit() {
+  static const int limit = [] {
+    if (hipFuncSetAttribute((const void*)select_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            160 * 1024) == hipSuccess)
+      return 160 * 1024;
+    (void)hipGetLastError();
+    return 64 * 1024;
+  }();
+  return limit;
+}
 
 void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int n_pin, int32_t* kept,
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
-  if (g_lds_limit < 0) {
-    g_lds_limit = 64 * 1024;
-    if (hipFuncSetAttribute((const void*)select_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024) == hipSuccess)
-      g_lds_limit = 160 * 1024;
-    else
-      (void)hipGetLastError();
-  }
   const int n_cand = L - n_stab - n_pin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
   if (wseg <= 12 * 64) {
@@ -325,7 +327,7 @@ void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_s
     return;
   }
   size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);
-  if (need <= (size_t)g_lds_limit)
+  if (need <= (size_t)lds_limit())
     hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, S, cap, L, n_keep, n_stab,
                        n_pin, kept, kept_stride, kept2, stride2);
   else
