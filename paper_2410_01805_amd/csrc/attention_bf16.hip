@@ -414,6 +414,7 @@ static int attn_variant() {      // read on every launch (cheap), so a process c
   int v = 4;
   if (e && !strcmp(e, "w8")) v = 0;
   if (e && !strcmp(e, "dma4")) v = 5;
+  if (e && !strcmp(e, "pp")) v = 6;
   if (e && !strcmp(e, "w4")) v = 1;
   if (e && !strcmp(e, "qb2")) v = 2;
   if (e && !strcmp(e, "pipe")) v = 3;
@@ -436,6 +437,7 @@ bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && (attn_variant(
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm) {
   const int v = attn_variant();
+  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
 #define LOCRET_CASE(DD)                                                                           \

@@ -231,17 +231,15 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
       float ps;
       auto exp_pack_sum = [&]() {
         float ps0 = 0.f, ps1 = 0.f;
-        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           uint32_t w[8];
 #pragma unroll
-          for (int r = 0; r < 16; r += 2)
-            w[r >> 1] = pack_bf16(__builtin_amdgcn_exp2f(sacc[kb][r]), __builtin_amdgcn_exp2f(sacc[kb][r + 1]));
-#pragma unroll
-          for (int i = 0; i < 8; i += 2) {
-            ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i]), ones, ps0, false);
-            ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i + 1]), ones, ps1, false);
+          for (int r = 0; r < 16; r += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(sacc[kb][r]), e1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1]);
+            w[r >> 1] = pack_bf16(e0, e1);
+            ps0 += e0;
+            ps1 += e1;
           }
           pb[kb * 2 + 0] = make_uint4(w[0], w[1], w[2], w[3]);
           pb[kb * 2 + 1] = make_uint4(w[4], w[5], w[6], w[7]);

@@ -1,0 +1,409 @@
+// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950, head_dim 128: the direct-to-LDS kernel
+// of attention_dma.hip with its two wavefronts per SIMD held in anti-phase.
+//
+// A wavefront's tile is a chain S (16 MFMAs) -> softmax (32 exp2 on the transcendental unit, ~640
+// cycles) -> PV (16 MFMAs).  Left alone, the two wavefronts of a SIMD drift into the same phase:
+// the older one wins every arbitration, runs its chain at full speed, and the younger one finishes
+// a pair of tiles ~30 % later, mostly alone on the SIMD with the matrix pipe idle during its softmax.
+// Here wavefronts 0..3 (group A, one per SIMD) and 4..7 (group B, their SIMD mates) are
+// offset by one S block with two workgroup barriers per tile:
+//
+//      barrier X(t) | A: S(t)                    | barrier Y(t) | A: softmax, PV, prefetch K frags of t+1
+//                   | B: loads of t+3, K frags t |              | B: S(t), softmax, PV
+//
+// so the matrix pipe sees S_A, S_B, PV_A, PV_B back to back while each softmax runs beside the
+// other group's MFMAs.  Group B issues all direct loads (8 per wavefront per tile) in the slot in
+// which it waits for A's S block; group A uses its slot at the end of the tile to fetch the first K
+// fragments of the next one.
+//
+// Ring of 4 stages, one tile per step.  Invariant at X(t): tiles t and t+1 have landed in LDS (B waits
+// for its own loads of tile t+2 before it arrives at X(t+1): s_waitcnt vmcnt(8) leaves only the 8 loads
+// of tile t+3 in flight) and every wavefront has finished tile t-1, whose stage the loads of tile t+3
+// overwrite.
+//
+// The V^T fragments are read with ds_read_b64_tr_b16 from inline assembly, with hand-counted
+// s_waitcnt lgkmcnt: the compiler puts an s_waitcnt vmcnt(0) in front of the intrinsic form (it
+// cannot tell that those reads never touch a stage with a load in flight), which would stall every
+// PV block on the loads just issued.  LDS operations return in order, so a count of the asm reads
+// issued after the wanted one is always sufficient, whatever else the compiler has in flight.
+//
+// Tile layout in LDS, swizzles, fragment addressing and the softmax are those of attention_dma.hip.
+#include <hip/hip_ext.h>
+
+#include "attn_common.h"
+#include "kernels.h"
+
+namespace locret {
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int PP_D = 128;
+constexpr int PP_TILE_B = KT * PP_D * 2;       // 16 KB per operand tile
+constexpr int PP_STAGE_B = 2 * PP_TILE_B;      // K then V
+constexpr int PP_NW = 8;
+constexpr int PP_KPRE = 4;                     // K fragments fetched ahead of the S block
+constexpr int PP_VPRE = 4;                     // V^T fragments in flight ahead of their MFMA
+
+#define LOCRET_TR_READ(dst, addr, off) \
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
+#define LOCRET_LGKM_WAIT(a, b, n) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "i"(n))
+
+__global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
+                                                             const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
+                                                             int Tn, int h, int g, int cap, int n_c, float c_log2,
+                                                             int hpw, int n_hgroups, int n_ttiles) {
+  constexpr int NW = PP_NW;
+  constexpr int D = PP_D;
+  constexpr int NKS = D / 16;
+  constexpr int NDB = D / 32;
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[4 * PP_STAGE_B];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n32 = lane & 31;
+  const int hi = lane >> 5;
+
+  const int bid = blockIdx.x;
+  int hgroup, tt;
+  if ((n_hgroups & 7) == 0) {                  // one KV head per XCD (workgroup ids go round the XCDs)
+    const int g8 = n_hgroups >> 3;
+    hgroup = (bid & 7) * g8 + (bid >> 3) % g8;
+    tt = bid / n_hgroups;
+  } else {
+    hgroup = bid % n_hgroups;
+    tt = bid / n_hgroups;
+  }
+  tt = n_ttiles - 1 - tt;                      // longest key ranges first
+  const int wph = NW / hpw;
+  const int TW = wph * 32;
+  const int t0 = tt * TW;
+  const int j = hgroup * hpw + wave / wph;
+  const int m = (hgroup * hpw) / g;
+  const int tw0 = t0 + (wave % wph) * 32;
+  const int t_last_wg = min(Tn, t0 + TW) - 1;
+  const int n_keys = n_c + t_last_wg + 1;
+  const int n_tiles = (n_keys + KT - 1) / KT;
+  const int wave_last_slot = n_c + min(Tn - 1, tw0 + 31);
+  const int my_t = min(tw0 + n32, Tn - 1);
+  const int limit = n_c + my_t;
+
+  auto scalar_ptr = [](const bf16_t* p) -> const bf16_t* {
+    uint64_t a = (uint64_t)p;
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    uint32_t hi32 = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return (const bf16_t*)(((uint64_t)hi32 << 32) | lo);
+  };
+  const bf16_t* Kb = scalar_ptr(Kx + (int64_t)m * cap * D);
+  const bf16_t* Vb = scalar_ptr(V + (int64_t)m * cap * D);
+
+  bf16x8 qf[NKS];
+  {
+    const bf16_t* qp = q + ((int64_t)my_t * h + j) * D + hi * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
+    const float qscale = c_log2;                 // logits come out of the MFMA in log2 units
+    if (tab != nullptr) {
+      // un-rotated queries: rotate to position n_c + t here (pairs (i, i + D/2) sit in fragments ks
+      // and ks + NKS/2 of the same lane), round to bf16 as the append kernel would have
+      const float2* tp = tab + (int64_t)(n_c + my_t) * (D / 2) + hi * 8;
+#pragma unroll
+      for (int ks = 0; ks < NKS / 2; ++ks) {
+        float lo[8], up[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 cs = tp[ks * 16 + e];
+          const float a = (float)qf[ks][e], b = (float)qf[ks + NKS / 2][e];
+          lo[e] = (a * cs.x - b * cs.y) * qscale;
+          up[e] = (b * cs.x + a * cs.y) * qscale;
+        }
+        uint4 pl = make_uint4(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]), pack_bf16(lo[4], lo[5]), pack_bf16(lo[6], lo[7]));
+        uint4 pu = make_uint4(pack_bf16(up[0], up[1]), pack_bf16(up[2], up[3]), pack_bf16(up[4], up[5]), pack_bf16(up[6], up[7]));
+        qf[ks] = __builtin_bit_cast(bf16x8, pl);
+        qf[ks + NKS / 2] = __builtin_bit_cast(bf16x8, pu);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = (float)qf[ks][e] * qscale;
+        uint4 px = make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+        qf[ks] = __builtin_bit_cast(bf16x8, px);
+      }
+    }
+  }
+  f32x16 oacc[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = 0.f, l_run = 0.f;
+  // m_run is in log2 units and negm holds -m_run in all 16 registers: the first MFMA of every S
+  // chain takes it as its addend, so the accumulator ends as (logit - running max) and exp2 applies
+  // to it directly.  `fresh` (wave-uniform) is true until the first tile has set the max.
+  f32x16 negm;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+  bool fresh = true;
+
+  const bool isB = wave >= NW / 2;             // wave-uniform; wavefronts w and w + 4 share a SIMD
+
+  // ---- direct loads (group B): instruction i of a tile covers rows 4i .. 4i+3; wavefront w issues
+  // ---- instructions w%4 + 4u, so (i & 3) is the same for all of them ----------------------------------
+  const int w4 = wave & 3;
+  const int l_row = lane >> 4, l_pos = lane & 15;
+  const int k_vo = w4 * 1024 + l_row * 256 + ((l_pos ^ l_row ^ (w4 << 2)) * 16);   // + u * 4096 (scalar offset)
+  const int v_vo = w4 * 1024 + l_row * 256 + ((l_pos ^ (l_row << 2)) * 16);
+  auto issue = [&](int tile, int stage) __attribute__((always_inline)) {
+    const int tile_u = __builtin_amdgcn_readfirstlane(tile);
+    const int left = __builtin_amdgcn_readfirstlane(max(n_keys - tile_u * KT, 0) * (D * 2));   // 0 past the end
+    __amdgpu_buffer_rsrc_t kr =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + (int64_t)tile_u * (KT * D)), 0, left, 0x00020000);
+    __amdgpu_buffer_rsrc_t vr =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(Vb + (int64_t)tile_u * (KT * D)), 0, left, 0x00020000);
+    unsigned char* sb = ring + stage * PP_STAGE_B;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = w4 + u * 4;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, (lds_ptr_t)(sb + i * 1024), 16, k_vo, u * 4096, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = w4 + u * 4;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, (lds_ptr_t)(sb + PP_TILE_B + i * 1024), 16, v_vo, u * 4096, 0, 0);
+    }
+  };
+
+  // ---- fragment addresses (bytes inside a stage) ---------------------------------------------------
+  const int kx = n32 & 15;
+  const int k_base = n32 * 256 + ((kx >> 1) << 5) + ((hi ^ (kx & 1)) << 4);
+  int k_rd[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) k_rd[ks] = k_base ^ (ks << 5);
+  const int vs = lane & 15, vG = lane >> 4;
+  const int v_base = PP_TILE_B + (((vG >> 1) * 4 + (vs >> 2)) * 256) + ((vs >> 2) << 6) +
+                     ((((vG & 1) << 1) + ((vs & 3) >> 1)) << 4) + ((vs & 1) << 3);
+  // LDS byte addresses of stage 0 for the asm reads
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)(lds_u8_ptr)ring;
+  uint32_t v_ad[NDB];
+#pragma unroll
+  for (int db = 0; db < NDB; ++db) v_ad[db] = ring_lds + (uint32_t)(v_base ^ (db << 6));
+
+  bf16x8 kpre[PP_KPRE];                          // fragment f = ks * 2 + kb of the tile whose S block comes next
+  auto prefetch_k = [&](int sb_off) __attribute__((always_inline)) {
+    const unsigned char* sb = ring + sb_off;
+#pragma unroll
+    for (int f = 0; f < PP_KPRE; ++f) kpre[f] = *(const bf16x8*)(sb + k_rd[f >> 1] + (f & 1) * 32 * 256);
+  };
+
+  auto s_block = [&](f32x16 (&sacc)[2], int sb_off) __attribute__((always_inline)) {
+    const unsigned char* sb = ring + sb_off;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) sacc[kb] = negm;   // the S chain starts from -(running max)
+    bf16x8 kf[NKS][2];
+#pragma unroll
+    for (int f = 0; f < 2 * NKS; ++f)
+      kf[f >> 1][f & 1] = f < PP_KPRE ? kpre[f] : *(const bf16x8*)(sb + k_rd[f >> 1] + (f & 1) * 32 * 256);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], sacc[kb], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 2 * NKS - PP_KPRE; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, PP_KPRE, 0);
+  };
+
+  // softmax and PV of one tile; the S accumulators are in sacc
+  auto softmax_pv = [&](f32x16 (&sacc)[2], int tile, int sb_off) __attribute__((always_inline)) {
+    const int base = tile * KT;
+    uint32_t va[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) va[db] = v_ad[db] + (uint32_t)sb_off;
+    // V^T fragment f = kc * NDB + db: two transposing 8-byte reads (keys +0..3 and +8..11 of the 16-key chunk)
+    s16x4 vlo[4 * NDB], vhi[4 * NDB];
+#pragma unroll
+    for (int f = 0; f < PP_VPRE; ++f) {
+      LOCRET_TR_READ(vlo[f], va[f % NDB], (f / NDB) * 4096);
+      LOCRET_TR_READ(vhi[f], va[f % NDB], (f / NDB) * 4096 + 2048);
+    }
+    if (base + KT - 1 > n_c + tw0) {           // wave-uniform: tile crosses the diagonal
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int slot = base + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
+          if (slot > limit) sacc[kb][r] = -INFINITY;
+        }
+    }
+    uint4 pb[4];
+    {
+      float ps;
+      auto exp_pack_sum = [&]() __attribute__((always_inline)) {
+        float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          uint32_t w[8];
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(sacc[kb][r]), e1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1]);
+            w[r >> 1] = pack_bf16(e0, e1);
+            ps0 += e0;
+            ps1 += e1;
+          }
+          pb[kb * 2 + 0] = make_uint4(w[0], w[1], w[2], w[3]);
+          pb[kb * 2 + 1] = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+        ps = ps0 + ps1;
+      };
+      exp_pack_sum();
+      if (fresh || __any(!(ps < 256.f))) {     // rare: move the running max (see attention_dma.hip)
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+        mx = max_across_halves(mx);
+        const float delta = fresh ? mx : fmaxf(mx, 0.f);
+        const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-delta);
+        m_run += delta;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negm[r] = -m_run;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[kb][r] -= delta;
+        fresh = false;
+        exp_pack_sum();
+      }
+      l_run += ps;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int f = 0; f < 4 * NDB; ++f) {
+      constexpr int LASTF = 4 * NDB - 1;
+      const int newest = f + PP_VPRE - 1 < LASTF ? f + PP_VPRE - 1 : LASTF;   // newest fragment already requested
+      // reads issued after fragment f's: two per fragment
+      static_assert(PP_VPRE <= 6, "lgkmcnt cases");
+      switch (2 * (newest - f)) {
+        case 10: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 10); break;
+        case 8: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 8); break;
+        case 6: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 6); break;
+        case 4: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 4); break;
+        case 2: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 2); break;
+        default: LOCRET_LGKM_WAIT(vlo[f], vhi[f], 0); break;
+      }
+      const s16x8 both = __builtin_shufflevector(vlo[f], vhi[f], 0, 1, 2, 3, 4, 5, 6, 7);
+      oacc[f % NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), *(const bf16x8*)&pb[f / NDB],
+                                                              oacc[f % NDB], 0, 0, 0);
+      if (f + PP_VPRE < 4 * NDB) {
+        const int fn = f + PP_VPRE;
+        LOCRET_TR_READ(vlo[fn], va[fn % NDB], (fn / NDB) * 4096);
+        LOCRET_TR_READ(vhi[fn], va[fn % NDB], (fn / NDB) * 4096 + 2048);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  auto wg_barrier = []() __attribute__((always_inline)) {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // tiles this wavefront's queries can see (wave-uniform, <= n_tiles): later tiles only keep the barriers
+  const int n_active = min(n_tiles, wave_last_slot / KT + 1);
+  if (isB) {
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");            // tiles 0 and 1 have landed
+    wg_barrier();
+    for (int t = 0; t < n_active; ++t) {
+      const int sb_off = (t & 3) * PP_STAGE_B;
+      wg_barrier();                                              // X(t)
+      issue(t + 3, (t + 3) & 3);
+      prefetch_k(sb_off);
+      wg_barrier();                                              // Y(t)
+      f32x16 sacc[2];
+      s_block(sacc, sb_off);
+      softmax_pv(sacc, t, sb_off);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");          // own loads of tile t+2 have landed
+    }
+    for (int t = n_active; t < n_tiles; ++t) {
+      wg_barrier();
+      issue(t + 3, (t + 3) & 3);
+      wg_barrier();
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    }
+  } else {
+    wg_barrier();
+    prefetch_k(0);
+    for (int t = 0; t < n_active; ++t) {
+      const int sb_off = (t & 3) * PP_STAGE_B;
+      wg_barrier();                                              // X(t)
+      f32x16 sacc[2];
+      s_block(sacc, sb_off);
+      wg_barrier();                                              // Y(t)
+      softmax_pv(sacc, t, sb_off);
+      prefetch_k(((t + 1) & 3) * PP_STAGE_B);
+    }
+    for (int t = n_active; t < n_tiles; ++t) {
+      wg_barrier();
+      wg_barrier();
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // trailing empty loads
+
+  // ---- epilogue ---------------------------------------------------------------------------------
+  {
+    const int t = tw0 + n32;
+    float l = l_run + __shfl_xor(l_run, 32, 64);
+    if (t < Tn) {
+      const float inv = 1.f / l;
+      bf16_t* op = out + ((int64_t)t * h + j) * D;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          uint2 w;
+          w.x = pack_bf16(oacc[db][rq * 4 + 0] * inv, oacc[db][rq * 4 + 1] * inv);
+          w.y = pack_bf16(oacc[db][rq * 4 + 2] * inv, oacc[db][rq * 4 + 3] * inv);
+          *(uint2*)(op + db * 32 + rq * 8 + hi * 4) = w;
+        }
+    }
+  }
+}
+
+// `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
+bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
+                              int T, int n_c, float scale, hipStream_t st) {
+  if (Dm.d != PP_D) return false;
+  if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
+  constexpr int NW = PP_NW;
+  const int g = Dm.g;
+  const int hpw = (g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
+  const int wph = NW / hpw;
+  const int TW = wph * 32;
+  const int n_hgroups = Dm.h / hpw;
+  const int n_ttiles = (T + TW - 1) / TW;
+  const float c_log2 = scale * 1.4426950408889634f;
+  hipExtLaunchKernelGGL(attn_pp_kernel, dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
+                        (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
+                        c_log2, hpw, n_hgroups, n_ttiles);
+  return true;
+}
+
+}  // namespace locret

@@ -61,6 +61,9 @@ bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, co
 // covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
 bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                                int T, int n_c, float scale, hipStream_t st);
+// The same kernel with the two wavefronts of every SIMD held one S block apart (attention_pp.hip).
+bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx,
+                              const void* V, void* out, int T, int n_c, float scale, hipStream_t st);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr,
