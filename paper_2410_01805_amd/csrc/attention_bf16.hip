@@ -405,16 +405,17 @@ static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const flo
                      n_hgroups, n_ttiles);
 }
 
-// LOCRET_ATTN_VARIANT selects a kernel for experiments: default "dma" (direct-to-LDS staging,
-// attention_dma.hip; head_dim 128 only, other head dims fall through to "w8"); "dma4" its
+// LOCRET_ATTN_VARIANT selects a kernel for experiments: default "pp" (direct-to-LDS staging with the two
+// wavefronts of a SIMD in anti-phase, attention_pp.hip; head_dim 128 only, other head dims fall through
+// to "w8"); "dma" the same staging with free-running wavefronts (attention_dma.hip), "dma4" its
 // 4-wavefront form; "w8" register-staged, 8 wavefronts per workgroup; "w4" 4 wavefronts, two
 // workgroups per CU; "qb2" 4 wavefronts with 64 queries each; "pipe" attention_pipe.hip.
 static int attn_variant() {      // read on every launch (cheap), so a process can compare variants
   const char* e = getenv("LOCRET_ATTN_VARIANT");
-  int v = 4;
+  int v = 6;
   if (e && !strcmp(e, "w8")) v = 0;
+  if (e && !strcmp(e, "dma")) v = 4;
   if (e && !strcmp(e, "dma4")) v = 5;
-  if (e && !strcmp(e, "pp")) v = 6;
   if (e && !strcmp(e, "w4")) v = 1;
   if (e && !strcmp(e, "qb2")) v = 2;
   if (e && !strcmp(e, "pipe")) v = 3;

@@ -118,11 +118,12 @@ def test_teacher_forced_stream_with_pinned_query_prefix():
     layer.close()
 
 
-@pytest.mark.parametrize("variant", ["dma4", "w8", "w4", "qb2", "pipe"])
+@pytest.mark.parametrize("variant", ["dma", "dma4", "w8", "w4", "qb2", "pipe"])
 @pytest.mark.parametrize("kw", [SMALL[4], SMALL[7]], ids=["bf16_llama_like", "bf16_ns_gt_B"])
 def test_alternative_attention_kernels(kw, variant, monkeypatch):
-    # LOCRET_ATTN_VARIANT selects other forms of the head_dim-128 attention kernel (register-staged,
-    # 4-wavefront, 64 queries per wavefront, half-tile pipeline); each must meet the same bar
+    # LOCRET_ATTN_VARIANT selects other forms of the head_dim-128 attention kernel (free-running
+    # direct-to-LDS, register-staged, 4-wavefront, 64 queries per wavefront, half-tile pipeline); each
+    # must meet the same bar
     monkeypatch.setenv("LOCRET_ATTN_VARIANT", variant)
     w = synth.tiny(**kw)
     layer, o, _ = _run_stream(w, teacher_forced=True)
