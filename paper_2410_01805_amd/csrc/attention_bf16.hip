@@ -274,21 +274,20 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
             if (slot > limit) sacc[kb][qb][r] = -INFINITY;
           }
       }
-      // exponentiate, pack to bf16, and sum the packed probabilities two per instruction
+      // exponentiate, pack to bf16 and sum (plain adds: v_dot2c shares the matrix pipe and queues behind
+      // the other wavefront's MFMAs)
       float ps;
       auto exp_pack_sum = [&]() {
         float ps0 = 0.f, ps1 = 0.f;
-        const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
           uint32_t w[8];
 #pragma unroll
-          for (int r = 0; r < 16; r += 2)
-            w[r >> 1] = pack_bf16(__builtin_amdgcn_exp2f(sacc[kb][qb][r]), __builtin_amdgcn_exp2f(sacc[kb][qb][r + 1]));
-#pragma unroll
-          for (int i = 0; i < 8; i += 2) {
-            ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i]), ones, ps0, false);
-            ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[i + 1]), ones, ps1, false);
+          for (int r = 0; r < 16; r += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(sacc[kb][qb][r]), e1 = __builtin_amdgcn_exp2f(sacc[kb][qb][r + 1]);
+            w[r >> 1] = pack_bf16(e0, e1);
+            ps0 += e0;
+            ps1 += e1;
           }
           pb[qb][kb * 2 + 0] = make_uint4(w[0], w[1], w[2], w[3]);
           pb[qb][kb * 2 + 1] = make_uint4(w[4], w[5], w[6], w[7]);

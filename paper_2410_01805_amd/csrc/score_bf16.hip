@@ -8,8 +8,11 @@
 // one of q, k, v and is fetched from that tensor directly.
 //
 // Operand staging goes global -> LDS without passing through registers (buffer_load ... lds,
-// 16 bytes per lane) into a ring of four stages, so three stages are always in flight: with one
-// workgroup of four wavefronts per CU it is this depth, not occupancy, that hides memory latency.
+// 16 bytes per lane) into a ring of four stages, so three stages are always in flight.  A direct load
+// holds its wavefront's issue slot for 60-80 cycles while the CU's vector-memory path (64 B/clk) is
+// busy, and a stage needs 32 of them: issued by the computing wavefronts they cost as much time as the
+// stage's 16 MFMAs.  So the workgroup has eight wavefronts: 0..3 only compute, 4..7 (their SIMD mates)
+// only issue loads, one barrier per stage between them.
 // Such a load writes lane L's 16 bytes at LDS base + 16 L, so an instruction fills 8 rows of 128
 // bytes back to back; bank conflicts are avoided by permuting WHICH 16-byte chunk a lane fetches:
 // position c' of row r holds chunk c' ^ ((r >> 1) & 7), and a fragment read of logical chunk c goes to
@@ -40,14 +43,14 @@ struct ScoreSmem {
     unsigned char ring[RT_STAGES * RT_STAGE_B];       // 128 KB
     struct {
       float W2s[RT_M * 32];          // [hidden][m-chunk of up to 32]
-      float red[2 * RT_N * 32];      // [wm][token][m-chunk]
+      float red[2 * RT_N * 33];      // [wm][token][m-chunk], rows padded to 33 floats (bank spread)
     } ep;
   };
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-__global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, int Tn, int hd, int kvd,
                                                          const bf16_t* __restrict__ W1t,
                                                          const float* __restrict__ W2f, int K, int h_kv,
@@ -57,7 +60,9 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n32 = lane & 31, hi = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;
+  const bool producer = wave >= 4;               // wave-uniform
+  const int pw = wave & 3;                       // producer: fills rows pw*32 .. pw*32+31 of both tiles
+  const int wm = (wave >> 1) & 1, wn = wave & 1; // consumer: 64 x 64 sub-tile
   const int t0 = blockIdx.x * RT_N;
   const int nb = blockIdx.y;
   const int r0 = nb * RT_M;
@@ -70,14 +75,14 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  // ---- loads: wavefront w fills rows w*32 .. w*32+31 of both tiles, 8 rows per instruction -------
+  // ---- loads: producer p fills rows p*32 .. p*32+31 of both tiles, 8 rows per instruction --------
   const int l_row = lane >> 3;                           // row inside the instruction's 8 rows
   // byte offset of the chunk this lane fetches: row = 8 * instruction + l_row, so (row >> 1) & 7 is
   // (l_row >> 1) for even instructions and (l_row >> 1) ^ 4 for odd ones (ii & 1 below)
   const int l_csw0 = ((lane & 7) ^ (l_row >> 1)) * 16;
   const int l_csw1 = ((lane & 7) ^ (l_row >> 1) ^ 4) * 16;
-  const int a_vo = (wave * 32 + l_row) * (K * 2);        // + ii * 8 rows + chunk offset
-  const int b_row = wave * 32 + l_row;                   // + ii * 8
+  const int a_vo = (pw * 32 + l_row) * (K * 2);        // + ii * 8 rows + chunk offset
+  const int b_row = pw * 32 + l_row;                     // + ii * 8
   const int n_stages = K / RT_K;
   const int q_stages = hd / RT_K, k_stages = kvd / RT_K;
   const int rows_left = min(max(Tn - t0, 0), RT_N);    // valid token rows of this workgroup
@@ -92,7 +97,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int ii = 0; ii < 4; ++ii)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            ar, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + (wave * 4 + ii) * 1024), 16, a_vo + ii * 8 * (K * 2) + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
+            ar, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + (pw * 4 + ii) * 1024), 16, a_vo + ii * 8 * (K * 2) + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
     }
     {
       const bf16_t* src;
@@ -107,7 +112,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int ii = 0; ii < 4; ++ii)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (wave * 4 + ii) * 1024), 16,
+            br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (pw * 4 + ii) * 1024), 16,
             (b_row + ii * 8) * rowb + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
     }
   };
@@ -121,11 +126,31 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
     b_rd[ks] = RT_TILE_B + (wn * 64 + n32) * 128 + pos;
   }
 
+  // The fragments of contraction steps 0 and 1 of a stage are requested at the end of the stage before
+  // (its data is already in LDS then, see the invariant below), so the MFMAs start right behind the barrier.
+  bf16x8 pre[8];
+  auto prefetch = [&](int buf) {
+    const unsigned char* base = sm.ring + buf * RT_STAGE_B;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      pre[ks * 4 + 0] = *(const bf16x8*)(base + a_rd[ks]);
+      pre[ks * 4 + 1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
+      pre[ks * 4 + 2] = *(const bf16x8*)(base + b_rd[ks]);
+      pre[ks * 4 + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
+    }
+  };
   auto compute = [&](int buf) {
     const unsigned char* base = sm.ring + buf * RT_STAGE_B;
     bf16x8 af[4][2], bfr[4][2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < 2; ++ks) {
+      af[ks][0] = pre[ks * 4 + 0];
+      af[ks][1] = pre[ks * 4 + 1];
+      bfr[ks][0] = pre[ks * 4 + 2];
+      bfr[ks][1] = pre[ks * 4 + 3];
+    }
+#pragma unroll
+    for (int ks = 2; ks < 4; ++ks) {
       af[ks][0] = *(const bf16x8*)(base + a_rd[ks]);
       af[ks][1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
       bfr[ks][0] = *(const bf16x8*)(base + b_rd[ks]);
@@ -138,8 +163,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][0], acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][1], acc[1][1], 0, 0, 0);
     }
-    // issue order: 8 fragment reads ahead, then one MFMA per remaining read
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    // issue order: one of the 8 remaining fragment reads behind each of the first 8 MFMAs
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -148,29 +172,38 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
     __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
   };
 
-  // one ring step: stage s is complete once at most 2 stages (16 loads of this wavefront) are still
-  // in flight; after the barrier every wavefront's part of stage s is in LDS and nobody reads the
-  // buffer of stage s-1 any more, which is where stage s+3 goes
-  auto step = [&](int s, int buf) {
-    // a bare barrier: __syncthreads() would first drain every load in flight (they count as
-    // memory writes), which is exactly what the ring is there to avoid
-    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    // compute first: the MFMAs of this stage are queued before the wavefront spends its issue slots on
-    // the direct loads of stage s + 3 (they go into the slot every wavefront left before this barrier)
-    compute(buf);
-    issue(s + RT_STAGES - 1, (buf + RT_STAGES - 1) % RT_STAGES);
-  };
-
-  issue(0, 0);
-  issue(1, 1);
-  issue(2, 2);
-  for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
-    step(s0, 0);
-    if (s0 + 1 < n_stages) step(s0 + 1, 1);
-    if (s0 + 2 < n_stages) step(s0 + 2, 2);
-    if (s0 + 3 < n_stages) step(s0 + 3, 3);
+  // One barrier per stage.  Invariant at barrier s: stages up to s+1 are in LDS (a producer arrives once at
+  // most one stage = 8 of its loads is still in flight) and every consumer has left stage s-1.  Behind it a
+  // producer starts stage s+3 in the buffer of stage s-1; a consumer computes stage s and then requests the
+  // first fragments of stage s+1.  A bare s_barrier: __syncthreads() would first drain every load in flight.
+  if (producer) {
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
+#pragma unroll
+      for (int u = 0; u < RT_STAGES; ++u)
+        if (s0 + u < n_stages) {
+          asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+          issue(s0 + u + RT_STAGES - 1, (u + RT_STAGES - 1) % RT_STAGES);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // trailing empty loads must land before LDS is reused
+  } else {
+    asm volatile("s_barrier" ::: "memory");
+    prefetch(0);
+    for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
+#pragma unroll
+      for (int u = 0; u < RT_STAGES; ++u)
+        if (s0 + u < n_stages) {
+          compute(u);
+          if (s0 + u + 1 < n_stages) {
+            prefetch((u + 1) % RT_STAGES);
+            asm volatile("s_barrier" ::: "memory");
+          }
+        }
+    }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // trailing empty loads must land before LDS is reused
 
   // ---- epilogue: SiLU in place, then W2 in chunks of up to 32 KV heads ---------------------------
 #pragma unroll
@@ -185,12 +218,12 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
   for (int m0 = 0; m0 < h_kv; m0 += 32) {
     const int mc = min(32, h_kv - m0);
     __syncthreads();                               // ring / previous chunk no longer read
-    for (int i = tid; i < RT_M * mc; i += 256) {
+    for (int i = tid; i < RT_M * mc; i += 512) {
       int hh = i / mc, mm = i % mc;
       sm.ep.W2s[hh * 32 + mm] = W2f[(int64_t)(r0 + hh) * h_kv + m0 + mm];
     }
     __syncthreads();
-    for (int mm = 0; mm < mc; ++mm) {
+    for (int mm = 0; mm < mc && !producer; ++mm) {
       float s0 = 0.f, s1 = 0.f;                    // token blocks b = 0, 1
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -204,16 +237,16 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t* __restric
       s0 += __shfl_xor(s0, 32, 64);
       s1 += __shfl_xor(s1, 32, 64);
       if (hi == 0) {
-        sm.ep.red[(wm * RT_N + wn * 64 + n32) * 32 + mm] = s0;
-        sm.ep.red[(wm * RT_N + wn * 64 + 32 + n32) * 32 + mm] = s1;
+        sm.ep.red[(wm * RT_N + wn * 64 + n32) * 33 + mm] = s0;
+        sm.ep.red[(wm * RT_N + wn * 64 + 32 + n32) * 33 + mm] = s1;
       }
     }
     __syncthreads();
-    for (int i = tid; i < RT_N * mc; i += 256) {
+    for (int i = tid; i < RT_N * mc; i += 512) {
       int tl = i % RT_N, mm = i / RT_N;
       int t = t0 + tl;
       if (t < Tn)
-        part[((int64_t)nb * h_kv + m0 + mm) * part_T + t] = sm.ep.red[tl * 32 + mm] + sm.ep.red[(RT_N + tl) * 32 + mm];
+        part[((int64_t)nb * h_kv + m0 + mm) * part_T + t] = sm.ep.red[tl * 33 + mm] + sm.ep.red[(RT_N + tl) * 33 + mm];
     }
   }
 }
@@ -229,7 +262,7 @@ int score_parts_bf16(const Dims& D) {
 void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T, const void* W1t,
                        const float* W2f, float* part, hipStream_t st) {
   dim3 grid((T + RT_N - 1) / RT_N, D.d_R / RT_M);
-  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                      (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T);
 }
 
