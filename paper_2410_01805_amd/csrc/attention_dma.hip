@@ -9,9 +9,12 @@
 // ALU overlap only partly, so every VALU instruction per tile costs time): the queries are scaled
 // by scale * log2(e) when they are loaded, and the S chain starts from an accumulator that holds
 // -(running max), so the MFMA result is already the exponent; per tile the VALU then only does the
-// 32 exp2, 16 bf16 packs and 16 two-way dot products that sum the packed probabilities.  The
-// running max moves only on the first tile and when a lane's probability sum reaches 2^8: no row
-// max is formed otherwise.
+// 32 exp2, 16 bf16 packs and 32 adds (v_dot2c over the packed pairs would halve the adds, but it
+// shares the matrix pipe and queues behind the other wavefront's MFMAs).  The running max moves only
+// on the first tile and when a lane's probability sum reaches 2^8: no row max is formed otherwise.
+//
+// This kernel lets its wavefronts run freely between barriers; attention_pp.hip is the same kernel
+// with the two wavefronts of a SIMD held in anti-phase, and is the one launched by default.
 //
 // LDS layout of one ring stage (32 KB): K tile then V tile, both [64 keys][128 dims] row-major,
 // 256 bytes per row, no padding.  A direct load writes lane L's 16 bytes at base + 16 L, i.e. one
@@ -226,8 +229,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
     }
     uint4 pb[4];
     {
-      // The accumulator holds (logit - running max) in log2 units: exponentiate, pack to bf16, and sum
-      // the packed probabilities (as the V product will see them) two per instruction.
+      // The accumulator holds (logit - running max) in log2 units: exponentiate, pack to bf16, and sum.
       float ps;
       auto exp_pack_sum = [&]() {
         float ps0 = 0.f, ps1 = 0.f;
