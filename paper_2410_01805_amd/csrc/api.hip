@@ -217,25 +217,34 @@ static void run_score(locret_ctx* c, const void* q, const void* k, const void* v
   launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st);
 }
 
-// select + compact on the live copy, whose rows [0, L) are filled; updates the host bookkeeping
-static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, hipStream_t st) {
+// the selection over the live copy's rows [0, L)
+static SelectArgs select_args(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out) {
   const int b = c->cfg.budget;
   const int n_keep = L < b ? L : b;
   const int ns = n_stab < L ? n_stab : L;
   const int npin = c->n_pin < L - ns ? c->n_pin : L - ns;     // the prefix covers what the stabilizers leave
   CacheBuf A = c->buf(c->cur);
-  int32_t* kept = (int32_t*)(c->ws + c->L.kept);
+  return SelectArgs{A.S, c->D.cap, L, n_keep, ns, npin, (int32_t*)(c->ws + c->L.kept), b, kept_idx_out, b};
+}
+
+// select + compact on the live copy, whose rows [0, L) are filled; updates the host bookkeeping.
+// select_done: the selection has already been launched (inside the attention launch).
+static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, hipStream_t st, bool select_done = false) {
+  const int b = c->cfg.budget;
+  const SelectArgs a = select_args(c, L, n_stab, kept_idx_out);
+  CacheBuf A = c->buf(c->cur);
   c->mark(3, 0, st);
-  launch_select(A.S, c->D.cap, c->D.h_kv, L, n_keep, ns, npin, kept, b, kept_idx_out, b, st);
+  if (!select_done)
+    launch_select(a.S, a.cap, c->D.h_kv, a.L, a.n_keep, a.n_stab, a.n_pin, a.kept, a.kept_stride, a.kept2, a.stride2, st);
   c->mark(3, 1, st);
   c->mark(4, 0, st);
   if (L > b) {
     CacheBuf B = c->buf(c->cur ^ 1);
-    launch_compact(c->D, A, B, kept, b, n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
+    launch_compact(c->D, A, B, a.kept, b, a.n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
     c->cur ^= 1;
   }
   c->mark(4, 1, st);
-  c->n_c = n_keep;
+  c->n_c = a.n_keep;
 }
 
 int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, int32_t n_stab,
@@ -265,18 +274,18 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const void* Kx = D.rope ? A.Kr : A.K;
   const int n_c = c->n_c;
   const int L = n_c + T;
-  auto attention = [&]() {
+  auto attention = [&](const SelectArgs* sel) {
     // when profiling, the matrix-core kernels are timed through their own dispatch
     const bool prof = c->prof_calls < c->prof_max;
     if (c->mfma_attn && prof && attention_bf16_attaches_timer(D)) {
       LaunchTimer tm;
       tm.start = c->prof_event(1, 0);
       tm.stop = c->prof_event(1, 1);
-      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm);
+      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel);
       return;
     }
     c->mark(1, 0, st);
-    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr);
+    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, LaunchTimer(), sel);
     else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st);
     c->mark(1, 1, st);
   };
@@ -287,16 +296,31 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     c->mark(2, 1, st);
   };
   bool ok = true;
+  // The selection depends on the scores only.  Where the attention launch can carry it (head_dim-128 kernel,
+  // few enough candidates for its register-resident form) the retaining head runs first and the selection
+  // rides in the first workgroups of the attention launch; LOCRET_FUSE_SELECT=0 (read per call) keeps the
+  // separate launch.
+  const char* fs = getenv("LOCRET_FUSE_SELECT");
+  bool fuse_select = false;
+  SelectArgs sa{};
+  if (evict && !c->overlap && c->mfma_attn && !(fs && fs[0] == '0')) {
+    sa = select_args(c, L, n_stab, kept_idx_out);
+    fuse_select = attention_bf16_fuses_select(D, sa.L - sa.n_stab - sa.n_pin);
+  }
   if (evict && c->overlap) {
     scores();
     ok = ok && hipEventRecord(c->ev_fork, st) == hipSuccess;
     ok = ok && hipStreamWaitEvent(c->side, c->ev_fork, 0) == hipSuccess;
     run_evict(c, L, n_stab, kept_idx_out, c->side);
     ok = ok && hipEventRecord(c->ev_join, c->side) == hipSuccess;
-    attention();
+    attention(nullptr);
     ok = ok && hipStreamWaitEvent(st, c->ev_join, 0) == hipSuccess;
+  } else if (fuse_select) {
+    scores();
+    attention(&sa);
+    run_evict(c, L, n_stab, kept_idx_out, st, /*select_done=*/true);
   } else {
-    attention();
+    attention(nullptr);
     scores();
     if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
     else {

@@ -434,10 +434,14 @@ bool attention_bf16_attaches_timer(const Dims& Dm) {
 // every kernel here except the half-tile pipeline takes un-rotated queries and rotates them itself
 bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && (attn_variant() != 3 || dma_applies(Dm)); }
 
+bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
+  return Dm.bf16 && attn_variant() == 6 && dma_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
+}
+
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                           float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm) {
+                           float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel) {
   const int v = attn_variant();
-  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
+  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel)) return;
   if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
 #define LOCRET_CASE(DD)                                                                           \

@@ -32,6 +32,7 @@
 
 #include "attn_common.h"
 #include "kernels.h"
+#include "select_body.h"
 
 namespace locret {
 
@@ -46,6 +47,7 @@ constexpr int PP_STAGE_B = 2 * PP_TILE_B;      // K then V
 constexpr int PP_NW = 8;
 constexpr int PP_KPRE = 4;                     // K fragments fetched ahead of the S block
 constexpr int PP_VPRE = 4;                     // V^T fragments in flight ahead of their MFMA
+constexpr int PP_SEL_MAXR = 48;                // keys per thread of a selection workgroup (512 threads)
 
 #define LOCRET_TR_READ(dst, addr, off) \
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
@@ -54,7 +56,7 @@ constexpr int PP_VPRE = 4;                     // V^T fragments in flight ahead 
 __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                             int hpw, int n_hgroups, int n_ttiles) {
+                                                             int hpw, int n_hgroups, int n_ttiles, SelectArgs sel, int n_sel) {
   constexpr int NW = PP_NW;
   constexpr int D = PP_D;
   constexpr int NKS = D / 16;
@@ -67,11 +69,19 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   const int n32 = lane & 31;
   const int hi = lane >> 5;
 
-  const int bid = blockIdx.x;
+  // The first n_sel workgroups of the launch do not attend: each runs the top-k selection of one KV head
+  // (it depends on the scores only, which are complete before the launch) and retires after a few tens
+  // of microseconds, long before the attention workgroups that follow it on the same CU would have started
+  // their second round; the selection's latency disappears from the step.
+  if ((int)blockIdx.x < n_sel) {
+    select_reg_body<PP_SEL_MAXR, PP_NW * 64>(sel, blockIdx.x, (uint32_t*)ring);
+    return;
+  }
+  const int bid = blockIdx.x - n_sel;
   int hgroup, tt;
   if ((n_hgroups & 7) == 0) {                  // one KV head per XCD (workgroup ids go round the XCDs)
     const int g8 = n_hgroups >> 3;
-    hgroup = (bid & 7) * g8 + (bid >> 3) % g8;
+    hgroup = (blockIdx.x & 7) * g8 + (bid >> 3) % g8;
     tt = bid / n_hgroups;
   } else {
     hgroup = bid % n_hgroups;
@@ -388,8 +398,15 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
 }
 
 // `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
+bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
+  if (Dm.d != PP_D || (int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;
+  const int wseg = ((n_cand + PP_NW - 1) / PP_NW + 63) & ~63;
+  return wseg <= PP_SEL_MAXR * 64;
+}
+
+// `sel` non-null (and attention_pp_fuses_select true): the launch also performs that selection.
 bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                              int T, int n_c, float scale, hipStream_t st) {
+                              int T, int n_c, float scale, hipStream_t st, const SelectArgs* sel) {
   if (Dm.d != PP_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
   constexpr int NW = PP_NW;
@@ -400,9 +417,11 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipExtLaunchKernelGGL(attn_pp_kernel, dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
+  const int n_sel = sel ? Dm.h_kv : 0;
+  const SelectArgs sa = sel ? *sel : SelectArgs{};
+  hipExtLaunchKernelGGL(attn_pp_kernel, dim3(n_sel + n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
                         (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
-                        c_log2, hpw, n_hgroups, n_ttiles);
+                        c_log2, hpw, n_hgroups, n_ttiles, sa, n_sel);
   return true;
 }
 

@@ -14,6 +14,17 @@ struct LaunchTimer {
   hipEvent_t stop = nullptr;
 };
 
+// One selection (Section 3.3, Eq. 4 with the stabilizer mask of Section 3.4) for every KV head: scores S[m][cap],
+// units [0, L), n_keep kept per head = the first n_pin units, the best of the middle ones, the last n_stab.
+struct SelectArgs {
+  const float* S;
+  int cap, L, n_keep, n_stab, n_pin;
+  int32_t* kept;        // [h_kv][kept_stride] ascending unit indices
+  int kept_stride;
+  int32_t* kept2;       // optional second copy (caller's buffer), or NULL
+  int stride2;
+};
+
 struct Dims {
   int h;        // query heads
   int h_kv;     // KV heads
@@ -63,11 +74,16 @@ bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const
                                int T, int n_c, float scale, hipStream_t st);
 // The same kernel with the two wavefronts of every SIMD held one S block apart (attention_pp.hip).
 bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx,
-                              const void* V, void* out, int T, int n_c, float scale, hipStream_t st);
+                              const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
+                              const SelectArgs* sel = nullptr);
+bool attention_pp_fuses_select(const Dims& D, int n_cand);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr,
-                           LaunchTimer tm = LaunchTimer());
+                           LaunchTimer tm = LaunchTimer(), const SelectArgs* sel = nullptr);
+// True when launch_attention_bf16 would carry out a selection over n_cand candidates per head inside its
+// own launch (pass `sel`); otherwise the caller launches launch_select itself.
+bool attention_bf16_fuses_select(const Dims& D, int n_cand);
 // True when launch_attention_bf16 takes un-rotated queries plus the rotary table for these
 // dimensions (the kernel rotates them itself); otherwise it expects rotated queries.
 bool attention_bf16_rotates_q(const Dims& D);
@@ -93,6 +109,8 @@ void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* 
 // With n_parts == 1 this is a strided copy (used for caller-supplied scores).
 void launch_score_reduce(const float* part, int n_parts, int part_stride_T, int h_kv, int T, float* S,
                          int cap, int n_c, float* out, hipStream_t st);
+
+
 
 // Stabilizer-masked top-k per KV head over S[m][0..L): keeps the first n_pin, the last n_stab and the
 // best (n_keep - n_stab - n_pin) of the rest (score desc, index asc); kept[m][0..n_keep) ascending.

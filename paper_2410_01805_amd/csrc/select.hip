@@ -20,19 +20,12 @@
 // queue on two or three counters.
 #include "device_util.h"
 #include "kernels.h"
+#include "select_body.h"
 
 namespace locret {
 
-__device__ __forceinline__ uint32_t score_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;   // NaN: below every number
-  if (u == 0x80000000u) u = 0u;                     // -0 ties with +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
-constexpr int SEL_REP = 32;    // counter replicas per bin (= LDS banks)
 constexpr int SEL_HDR = 256 * SEL_REP + 256 + 128;   // words of LDS before the keys: hist[256][32] tot[256] wsum[64] bc[64]
 
 template <bool IN_LDS>
@@ -170,134 +163,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
 }
 
 // ------------------------------------------------------------------------------------------------
-// Register-resident variant: MAXR keys per thread.
+// Register-resident variant: MAXR keys per thread (select_body.h).
 template <int MAXR>
-__global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(const float* __restrict__ S, int cap, int L,
-                                                                 int n_keep, int n_stab, int n_pin,
-                                                                 int32_t* __restrict__ kept,
-                                                                 int kept_stride, int32_t* __restrict__ kept2,
-                                                                 int stride2) {
-  __shared__ uint32_t hist[256 * SEL_REP];
-  __shared__ uint32_t tot[256];
-  __shared__ uint32_t wsum[2 * SEL_WAVES];
-  __shared__ uint32_t bc[2];
-  const int m = blockIdx.x;
-  const float* s = S + (int64_t)m * cap + n_pin;   // candidate c is unit n_pin + c
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int n_cand = L - n_stab - n_pin;
-  const int kk = n_keep - n_stab - n_pin;
-  const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;     // <= MAXR * 64 (checked by the host)
-  const int w_lo = wave * wseg;
-  const int w_hi = min(n_cand, w_lo + wseg);
-  const int first = w_lo + lane;
-  const int nvalid = first < w_hi ? (w_hi - first + 63) >> 6 : 0;        // this thread's keys: rounds 0 .. nvalid-1
-
-  uint32_t k[MAXR];
-  {
-    float f[MAXR];
-#pragma unroll
-    for (int j = 0; j < MAXR; ++j) f[j] = (j < nvalid) ? s[first + j * 64] : 0.f;
-#pragma unroll
-    for (int j = 0; j < MAXR; ++j) k[j] = score_key(f[j]);
-  }
-
-  uint32_t tau, need_eq;
-  if (kk >= n_cand) {
-    tau = 0u; need_eq = 0xffffffffu;
-  } else if (kk == 0) {
-    tau = 0xffffffffu; need_eq = 0u;
-  } else {
-    uint32_t prefix = 0u, mask = 0u, remaining = (uint32_t)kk;
-    const int rep = lane & (SEL_REP - 1);
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      for (int i = tid; i < 256 * SEL_REP; i += SEL_THREADS) hist[i] = 0u;
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < MAXR; ++j)
-        if (j < nvalid && (k[j] & mask) == prefix) atomicAdd(&hist[((k[j] >> shift) & 255u) * SEL_REP + rep], 1u);
-      __syncthreads();
-      {
-        const int bin = tid >> 2, qtr = tid & 3;
-        uint32_t sum = 0;
-#pragma unroll
-        for (int r = 0; r < SEL_REP / 4; ++r) sum += hist[bin * SEL_REP + qtr * (SEL_REP / 4) + r];
-        sum += __shfl_xor(sum, 1, 64);
-        sum += __shfl_xor(sum, 2, 64);
-        if (qtr == 0) tot[bin] = sum;
-      }
-      __syncthreads();
-      if (wave == 0) {
-        const int b0 = 255 - 4 * lane;          // lane l owns bins 255-4l .. 252-4l, largest digit first
-        uint32_t c0 = tot[b0], c1 = tot[b0 - 1], c2 = tot[b0 - 2], c3 = tot[b0 - 3];
-        uint32_t sum4 = c0 + c1 + c2 + c3;
-        uint32_t incl = sum4;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          uint32_t y = __shfl_up(incl, o, 64);
-          if (lane >= o) incl += y;
-        }
-        uint32_t excl = incl - sum4;
-        if (excl < remaining && remaining <= incl) {
-          uint32_t r = remaining - excl;
-          uint32_t dgt, above;
-          if (r <= c0) { dgt = b0; above = excl; }
-          else if (r <= c0 + c1) { dgt = b0 - 1; above = excl + c0; }
-          else if (r <= c0 + c1 + c2) { dgt = b0 - 2; above = excl + c0 + c1; }
-          else { dgt = b0 - 3; above = excl + c0 + c1 + c2; }
-          bc[0] = prefix | (dgt << shift);
-          bc[1] = remaining - above;
-        }
-      }
-      __syncthreads();
-      prefix = bc[0];
-      remaining = bc[1];
-      mask |= 0xffu << shift;
-    }
-    tau = prefix;
-    need_eq = remaining;
-  }
-
-  // ordered compaction over the registers
-  uint32_t tot_gt = 0, tot_eq = 0;
-#pragma unroll
-  for (int j = 0; j < MAXR; ++j) {
-    tot_gt += __popcll(__ballot(j < nvalid && k[j] > tau));
-    tot_eq += __popcll(__ballot(j < nvalid && k[j] == tau));
-  }
-  if (lane == 0) { wsum[wave] = tot_gt; wsum[SEL_WAVES + wave] = tot_eq; }
-  __syncthreads();
-  uint32_t run_gt = 0, run_eq = 0;
-  for (int w = 0; w < wave; ++w) { run_gt += wsum[w]; run_eq += wsum[SEL_WAVES + w]; }
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  // kept list: pinned prefix [0, n_pin), then the chosen candidates, then the stabilizers
-  int32_t* out = kept + (int64_t)m * kept_stride + n_pin;
-  int32_t* out2 = kept2 ? kept2 + (int64_t)m * stride2 + n_pin : nullptr;
-  for (int i = tid; i < n_pin; i += SEL_THREADS) {
-    out[i - n_pin] = i;
-    if (out2) out2[i - n_pin] = i;
-  }
-#pragma unroll
-  for (int j = 0; j < MAXR; ++j) {
-    const bool gt = j < nvalid && k[j] > tau;
-    const bool eq = j < nvalid && k[j] == tau;
-    const uint64_t bg = __ballot(gt), be = __ballot(eq);
-    const uint32_t gt_before = run_gt + __popcll(bg & lt_mask);
-    const uint32_t eq_before = run_eq + __popcll(be & lt_mask);
-    if (gt || (eq && eq_before < need_eq)) {
-      const uint32_t pos = gt_before + min(eq_before, need_eq);
-      out[pos] = n_pin + first + j * 64;
-      if (out2) out2[pos] = n_pin + first + j * 64;
-    }
-    run_gt += __popcll(bg);
-    run_eq += __popcll(be);
-  }
-  for (int i = n_cand + tid; i < L - n_pin; i += SEL_THREADS) {
-    out[kk + (i - n_cand)] = n_pin + i;
-    if (out2) out2[kk + (i - n_cand)] = n_pin + i;
-  }
+__global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(SelectArgs a) {
+  __shared__ uint32_t smem[select_body_smem_words(SEL_THREADS)];
+  select_reg_body<MAXR, SEL_THREADS>(a, blockIdx.x, smem);
 }
 
 // bytes of dynamic LDS the in-LDS variant may use: asked for once (thread-safe static initialisation)
@@ -316,14 +186,13 @@ void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_s
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
   const int n_cand = L - n_stab - n_pin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
+  const SelectArgs a = {S, cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2};
   if (wseg <= 12 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, n_pin, kept,
-                       kept_stride, kept2, stride2);
+    hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;
   }
   if (wseg <= 24 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, S, cap, L, n_keep, n_stab, n_pin, kept,
-                       kept_stride, kept2, stride2);
+    hipLaunchKernelGGL(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;
   }
   size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);

@@ -130,6 +130,16 @@ def test_alternative_attention_kernels(kw, variant, monkeypatch):
     layer.close()
 
 
+def test_selection_as_its_own_launch(monkeypatch):
+    # by default the head_dim-128 attention launch carries the selection in its first workgroups;
+    # LOCRET_FUSE_SELECT=0 (read per call) launches it separately: same kept indices either way
+    monkeypatch.setenv("LOCRET_FUSE_SELECT", "0")
+    for kw in (SMALL[4], SMALL[7]):
+        w = synth.tiny(**kw)
+        layer, o, _ = _run_stream(w, teacher_forced=True)
+        layer.close()
+
+
 def test_plain_kernels_on_bf16_storage(monkeypatch):
     # LOCRET_FORCE_SIMPLE=1 (read when the context is created): the fp32 VALU attention and retaining
     # head also serve bf16 tensors
