@@ -203,8 +203,9 @@ int locret_reset(locret_ctx* c) {
   return LOCRET_OK;
 }
 
+// reduce = false: only the partial scores are formed (ws + L.part, *n_parts of them); the caller sums them
 static void run_score(locret_ctx* c, const void* q, const void* k, const void* v, int T, float* S_dst, int n_c,
-                      float* out, hipStream_t st) {
+                      float* out, hipStream_t st, bool reduce = true, int* n_parts = nullptr) {
   float* part = (float*)(c->ws + c->L.part);
   int parts;
   if (c->mfma_score) {
@@ -214,7 +215,8 @@ static void run_score(locret_ctx* c, const void* q, const void* k, const void* v
     launch_score_simple(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
     parts = score_parts_simple(c->D);
   }
-  launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st);
+  if (n_parts) *n_parts = parts;
+  if (reduce) launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st);
 }
 
 // the selection over the live copy's rows [0, L)
@@ -224,7 +226,8 @@ static SelectArgs select_args(locret_ctx* c, int L, int n_stab, int32_t* kept_id
   const int ns = n_stab < L ? n_stab : L;
   const int npin = c->n_pin < L - ns ? c->n_pin : L - ns;     // the prefix covers what the stabilizers leave
   CacheBuf A = c->buf(c->cur);
-  return SelectArgs{A.S, c->D.cap, L, n_keep, ns, npin, (int32_t*)(c->ws + c->L.kept), b, kept_idx_out, b};
+  return SelectArgs{A.S, c->D.cap, L, n_keep, ns, npin, (int32_t*)(c->ws + c->L.kept), b, kept_idx_out, b,
+                    nullptr, 0, 0, 0, 0, 0, nullptr, nullptr};
 }
 
 // select + compact on the live copy, whose rows [0, L) are filled; updates the host bookkeeping.
@@ -289,10 +292,24 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st);
     c->mark(1, 1, st);
   };
-  auto scores = [&]() {
+  auto scores = [&](SelectArgs* fused) {
     c->mark(2, 0, st);
-    run_score(c, q, k, v, T, scores_in ? nullptr : A.S, n_c, scores_out, st);
-    if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, n_c, nullptr, st);
+    if (fused && !scores_in) {
+      // the selection workgroups of the attention launch sum the partial scores themselves
+      int parts = 0;
+      run_score(c, q, k, v, T, nullptr, n_c, nullptr, st, /*reduce=*/false, &parts);
+      fused->part = (const float*)(c->ws + c->L.part);
+      fused->n_parts = parts;
+      fused->part_T = T;
+      fused->h_kv = D.h_kv;
+      fused->red_n_c = n_c;
+      fused->red_T = T;
+      fused->S_w = A.S;
+      fused->red_out = scores_out;
+    } else {
+      run_score(c, q, k, v, T, scores_in ? nullptr : A.S, n_c, scores_out, st);
+      if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, n_c, nullptr, st);
+    }
     c->mark(2, 1, st);
   };
   bool ok = true;
@@ -308,7 +325,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     fuse_select = attention_bf16_fuses_select(D, sa.L - sa.n_stab - sa.n_pin);
   }
   if (evict && c->overlap) {
-    scores();
+    scores(nullptr);
     ok = ok && hipEventRecord(c->ev_fork, st) == hipSuccess;
     ok = ok && hipStreamWaitEvent(c->side, c->ev_fork, 0) == hipSuccess;
     run_evict(c, L, n_stab, kept_idx_out, c->side);
@@ -316,12 +333,12 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     attention(nullptr);
     ok = ok && hipStreamWaitEvent(st, c->ev_join, 0) == hipSuccess;
   } else if (fuse_select) {
-    scores();
+    scores(&sa);
     attention(&sa);
     run_evict(c, L, n_stab, kept_idx_out, st, /*select_done=*/true);
   } else {
     attention(nullptr);
-    scores();
+    scores(nullptr);
     if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
     else {
       c->n_c = L;

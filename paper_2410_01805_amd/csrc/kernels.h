@@ -23,6 +23,13 @@ struct SelectArgs {
   int kept_stride;
   int32_t* kept2;       // optional second copy (caller's buffer), or NULL
   int stride2;
+  // Optional first step (register-resident form inside the attention launch only): sum the retaining
+  // head's partial scores part[p][m][t], p < n_parts in ascending order, into S_w[m][red_n_c + t] (the rows
+  // of S that the selection then reads) and red_out[m][t]; part == NULL: the scores are already in S.
+  const float* part;
+  int n_parts, part_T, h_kv, red_n_c, red_T;
+  float* S_w;
+  float* red_out;
 };
 
 struct Dims {

@@ -186,7 +186,8 @@ void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_s
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
   const int n_cand = L - n_stab - n_pin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
-  const SelectArgs a = {S, cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2};
+  const SelectArgs a = {S, cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2,
+                        nullptr, 0, 0, 0, 0, 0, nullptr, nullptr};
   if (wseg <= 12 * 64) {
     hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;

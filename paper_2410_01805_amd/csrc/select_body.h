@@ -27,6 +27,16 @@ __device__ __forceinline__ void select_reg_body(const SelectArgs& a, int m, uint
   uint32_t* bc = wsum + 2 * NWAVES;            // [2]
   const float* s = a.S + (int64_t)m * a.cap + a.n_pin;   // candidate c is unit n_pin + c
   const int tid = threadIdx.x;
+  if (a.part != nullptr) {
+    // the chunk's scores first: the same sum, in the same order, as score_reduce_kernel
+    for (int t = tid; t < a.red_T; t += NT) {
+      float sum = a.part[(int64_t)m * a.part_T + t];   // a single part is copied bit for bit (-0 stays -0)
+      for (int p = 1; p < a.n_parts; ++p) sum += a.part[((int64_t)p * a.h_kv + m) * a.part_T + t];
+      a.S_w[(int64_t)m * a.cap + a.red_n_c + t] = sum;
+      if (a.red_out) a.red_out[(int64_t)m * a.red_T + t] = sum;
+    }
+    __syncthreads();   // workgroup-scope release/acquire: the keys below are read back from S by other threads
+  }
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int L = a.L, n_pin = a.n_pin;
