@@ -212,8 +212,6 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
 
   auto s_block = [&](f32x16 (&sacc)[2], int sb_off) __attribute__((always_inline)) {
     const unsigned char* sb = ring + sb_off;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) sacc[kb] = negm;   // the S chain starts from -(running max)
     bf16x8 kf[NKS][2];
 #pragma unroll
     for (int f = 0; f < 2 * NKS; ++f)
@@ -222,7 +220,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], sacc[kb], 0, 0, 0);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], ks == 0 ? negm : sacc[kb], 0, 0, 0);   // the S chain starts from -(running max)
 #pragma unroll
     for (int i = 0; i < 2 * NKS - PP_KPRE; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
