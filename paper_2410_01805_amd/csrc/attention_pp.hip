@@ -47,6 +47,7 @@ constexpr int PP_STAGE_B = 2 * PP_TILE_B;      // K then V
 constexpr int PP_NW = 8;
 constexpr int PP_KPRE = 4;                     // K fragments fetched ahead of the S block
 constexpr int PP_VPRE = 4;                     // V^T fragments in flight ahead of their MFMA
+constexpr int PP_YTAIL = 4;                    // MFMAs of group A's S block issued behind barrier Y
 constexpr int PP_SEL_MAXR = 48;                // keys per thread of a selection workgroup (512 threads)
 
 #define LOCRET_TR_READ(dst, addr, off) \
@@ -210,23 +211,29 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
     for (int f = 0; f < PP_KPRE; ++f) kpre[f] = *(const bf16x8*)(sb + k_rd[f >> 1] + (f & 1) * 32 * 256);
   };
 
-  auto s_block = [&](f32x16 (&sacc)[2], int sb_off) __attribute__((always_inline)) {
+  // `mid` runs before the last `tail` MFMAs are issued (all fragment reads are out by then)
+  auto s_block = [&](f32x16 (&sacc)[2], int sb_off, auto mid, auto tail_c) __attribute__((always_inline)) {
+    constexpr int TAIL = decltype(tail_c)::value;    // 0: no split
     const unsigned char* sb = ring + sb_off;
     bf16x8 kf[NKS][2];
 #pragma unroll
     for (int f = 0; f < 2 * NKS; ++f)
       kf[f >> 1][f & 1] = f < PP_KPRE ? kpre[f] : *(const bf16x8*)(sb + k_rd[f >> 1] + (f & 1) * 32 * 256);
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], ks == 0 ? negm : sacc[kb], 0, 0, 0);   // the S chain starts from -(running max)
+    for (int f = 0; f < 2 * NKS - TAIL; ++f)
+      sacc[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[f >> 1][f & 1], qf[f >> 1], f < 2 ? negm : sacc[f & 1], 0, 0, 0);   // the S chain starts from -(running max)
 #pragma unroll
     for (int i = 0; i < 2 * NKS - PP_KPRE; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, PP_KPRE, 0);
+    if (TAIL < PP_KPRE) __builtin_amdgcn_sched_group_barrier(0x008, PP_KPRE - TAIL, 0);
+    if (TAIL > 0) {
+      mid();
+#pragma unroll
+      for (int f = 2 * NKS - TAIL; f < 2 * NKS; ++f)
+        sacc[f & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[f >> 1][f & 1], qf[f >> 1], sacc[f & 1], 0, 0, 0);
+    }
   };
 
   // softmax and PV of one tile; the S accumulators are in sacc
@@ -346,7 +353,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
       prefetch_k(sb_off);
       wg_barrier();                                              // Y(t)
       f32x16 sacc[2];
-      s_block(sacc, sb_off);
+      s_block(sacc, sb_off, []() {}, IntC<0>());
       softmax_pv(sacc, t, sb_off);
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");          // own loads of tile t+2 have landed
     }
@@ -363,8 +370,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
       const int sb_off = (t & 3) * PP_STAGE_B;
       wg_barrier();                                              // X(t)
       f32x16 sacc[2];
-      s_block(sacc, sb_off);
-      wg_barrier();                                              // Y(t)
+      s_block(sacc, sb_off, wg_barrier, IntC<PP_YTAIL>());        // Y(t), passed PP_YTAIL MFMAs before the end of the block
       softmax_pv(sacc, t, sb_off);
       prefetch_k(((t + 1) & 3) * PP_STAGE_B);
     }
