@@ -212,8 +212,10 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float z = acc[a][b][r];
-        acc[a][b][r] = z / (1.f + __expf(-z));
+        // SiLU(z) = z / (1 + 2^(-z log2 e)) with the hardware exp2 and reciprocal (1 ulp each: far inside
+        // what the bf16 operands of this kernel leave of the result)
+        const float z = acc[a][b][r];
+        acc[a][b][r] = z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z * -1.4426950408889634f));
       }
   for (int m0 = 0; m0 < h_kv; m0 += 32) {
     const int mc = min(32, h_kv - m0);
