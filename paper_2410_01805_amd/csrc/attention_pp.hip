@@ -14,7 +14,11 @@
 // so the matrix pipe sees S_A, S_B, PV_A, PV_B back to back while each softmax runs beside the
 // other group's MFMAs.  Group B issues all direct loads (8 per wavefront per tile) in the slot in
 // which it waits for A's S block; group A uses its slot at the end of the tile to fetch the first K
-// fragments of the next one.
+// fragments of the next one.  A passes Y four MFMAs before the end of its S block (all its fragment reads
+// are out by then), so B's first MFMAs queue behind A's last ones instead of meeting an idle pipe.
+//
+// The first workgroups of the launch can carry the step's selection (and the sum of the retaining head's
+// partial scores before it): see the kernel body and select_body.h.
 //
 // Ring of 4 stages, one tile per step.  Invariant at X(t): tiles t and t+1 have landed in LDS (B waits
 // for its own loads of tile t+2 before it arrives at X(t+1): s_waitcnt vmcnt(8) leaves only the 8 loads

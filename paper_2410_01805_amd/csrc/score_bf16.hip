@@ -50,6 +50,14 @@ struct ScoreSmem {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
+// sum over the two half-waves without a trip through LDS: after the swap one register holds the low half's
+// value in both halves and the other the high half's (the order of the two addends is the same in both halves)
+__device__ __forceinline__ float sum_across_halves(float x) {
+  const uint32_t u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, int Tn, int hd, int kvd,
                                                          const bf16_t* __restrict__ W1t,
@@ -88,8 +96,8 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   const int rows_left = min(max(Tn - t0, 0), RT_N);    // valid token rows of this workgroup
 
   auto issue = [&](int s, int buf) {
-    // past the last stage the descriptors are empty: the loads return zeros into a free buffer and
-    // keep the number of loads in flight constant for the wait counts below
+    // (a stage past the last one would get empty descriptors: zeros, no memory access; the loops below
+    // do not ask for one: 24 such loads per producer at the end kept every wavefront waiting ~4000 cycles)
     const bool live = s < n_stages;
     {
       __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc(
@@ -178,17 +186,20 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   // first fragments of stage s+1.  A bare s_barrier: __syncthreads() would first drain every load in flight.
   if (producer) {
     issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
+    if (1 < n_stages) issue(1, 1);
+    if (2 < n_stages) issue(2, 2);
     for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
 #pragma unroll
       for (int u = 0; u < RT_STAGES; ++u)
         if (s0 + u < n_stages) {
-          asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-          issue(s0 + u + RT_STAGES - 1, (u + RT_STAGES - 1) % RT_STAGES);
+          // at most stage s+2 may still be in flight; past the end nothing more is issued, and then the
+          // count has to drop to zero for stage s+1 to be known complete
+          if (s0 + u + 2 < n_stages) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+          else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          asm volatile("s_barrier" ::: "memory");
+          if (s0 + u + RT_STAGES - 1 < n_stages) issue(s0 + u + RT_STAGES - 1, (u + RT_STAGES - 1) % RT_STAGES);
         }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // trailing empty loads must land before LDS is reused
   } else {
     asm volatile("s_barrier" ::: "memory");
     prefetch(0);
@@ -236,8 +247,8 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
           s0 = fmaf(acc[a][0][r], w, s0);
           s1 = fmaf(acc[a][1][r], w, s1);
         }
-      s0 += __shfl_xor(s0, 32, 64);
-      s1 += __shfl_xor(s1, 32, 64);
+      s0 = sum_across_halves(s0);
+      s1 = sum_across_halves(s1);
       if (hi == 0) {
         sm.ep.red[(wm * RT_N + wn * 64 + n32) * 33 + mm] = s0;
         sm.ep.red[(wm * RT_N + wn * 64 + 32 + n32) * 33 + mm] = s1;
