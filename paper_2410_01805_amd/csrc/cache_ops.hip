@@ -162,6 +162,20 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
 // Compaction: dst[m][r] = src[m][kept[m][r]].  A thread owns slot r (and VEC rotary pairs of it)
 // for ALL KV heads: the rotary table row of slot r is read once and reused for every head, and
 // the loads of HB heads are issued together before anything is stored (memory-level parallelism).
+// 16-byte loads and stores that bypass the caches' retention: compaction touches every byte once
+typedef unsigned int nt_u32x4 __attribute__((ext_vector_type(4)));
+template <typename R>
+__device__ __forceinline__ R nt_load16(const void* p) {
+  static_assert(sizeof(R) == 16, "16-byte lanes");
+  nt_u32x4 v = __builtin_nontemporal_load((const nt_u32x4*)p);
+  return __builtin_bit_cast(R, v);
+}
+template <typename R>
+__device__ __forceinline__ void nt_store16(void* p, R r) {
+  static_assert(sizeof(R) == 16, "16-byte lanes");
+  __builtin_nontemporal_store(__builtin_bit_cast(nt_u32x4, r), (nt_u32x4*)p);
+}
+
 template <typename T, int HB>
 __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                       const float* __restrict__ Ss, const int32_t* __restrict__ Ps,
@@ -199,20 +213,20 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
     for (int u = 0; u < HB; ++u) {
       const int m = min(m0 + u, m_hi - 1);
       const int64_t srow = ((int64_t)m * cap + src[u]) * d;
-      klo[u].raw = *(const raw_t*)(Ks + srow + off);
-      khi[u].raw = *(const raw_t*)(Ks + srow + half + off);
-      vlo[u].raw = *(const raw_t*)(Vs + srow + off);
-      vhi[u].raw = *(const raw_t*)(Vs + srow + half + off);
+      klo[u].raw = nt_load16<raw_t>(Ks + srow + off);
+      khi[u].raw = nt_load16<raw_t>(Ks + srow + half + off);
+      vlo[u].raw = nt_load16<raw_t>(Vs + srow + off);
+      vhi[u].raw = nt_load16<raw_t>(Vs + srow + half + off);
     }
 #pragma unroll
     for (int u = 0; u < HB; ++u) {
       const int m = m0 + u;
       if (m >= m_hi) break;
       const int64_t drow = ((int64_t)m * cap + r) * d;
-      *(raw_t*)(Kd + drow + off) = klo[u].raw;
-      *(raw_t*)(Kd + drow + half + off) = khi[u].raw;
-      *(raw_t*)(Vd + drow + off) = vlo[u].raw;
-      *(raw_t*)(Vd + drow + half + off) = vhi[u].raw;
+      nt_store16(Kd + drow + off, klo[u].raw);
+      nt_store16(Kd + drow + half + off, khi[u].raw);
+      nt_store16(Vd + drow + off, vlo[u].raw);
+      nt_store16(Vd + drow + half + off, vhi[u].raw);
       if (rope) {
         V16 olo, ohi;
 #pragma unroll
@@ -221,8 +235,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
           olo.set(i, a * cs[i].x - b * cs[i].y);
           ohi.set(i, b * cs[i].x + a * cs[i].y);
         }
-        *(raw_t*)(Krd + drow + off) = olo.raw;
-        *(raw_t*)(Krd + drow + half + off) = ohi.raw;
+        nt_store16(Krd + drow + off, olo.raw);
+        nt_store16(Krd + drow + half + off, ohi.raw);
       }
       if (part == 0) {
         Sd[(int64_t)m * cap + r] = Ss[(int64_t)m * cap + src[u]];
