@@ -261,3 +261,25 @@ def test_profile_modes():
         B.locret_profile_mode(layer.ctx, 2)
     layer.close()
 
+
+@pytest.mark.parametrize("n_s", [24, 23], ids=["fits_the_fused_selection", "one_candidate_too_many"])
+def test_selection_inside_attention_at_its_size_limit(n_s):
+    # the head_dim-128 attention launch carries the selection while a wavefront's share of the candidates fits
+    # 48 rounds of 64 (24576 per head); one candidate more and the step launches the separate kernel (here its
+    # keys-in-LDS form).  Same kept indices either way; the oracle only scores and evicts (teacher-forced).
+    w = synth.tiny(name=f"sel_limit_{n_s}", dtype="bf16", h=4, h_kv=1, d=128, N=6 * 4600, B=4600, b=20000, n_s=n_s,
+                   d_R=128)
+    layer, W1, W2 = make_layer(w)
+    o = make_oracle(w, W1, W2)
+    for c in range(6):
+        q, k, v = synth.chunk(w, c)
+        sc_ref = o.score(q, k, v)
+        n_c = o.n_c
+        kept_ref = o.evict_compact(sc_ref, k, v, w.n_s)
+        _, _, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), w.n_s, scores_in=torch.from_numpy(sc_ref).to(DEV))
+        n_keep = min(n_c + w.B, w.b)
+        np.testing.assert_array_equal(kept.cpu().numpy()[:, :n_keep], kept_ref, err_msg=f"chunk {c}")
+    assert o.n_c == layer.cache_len == w.b
+    K, V, S, P = layer.cache_tensors()
+    np.testing.assert_array_equal(P[0].cpu().numpy(), o.P[0])
+    layer.close()
