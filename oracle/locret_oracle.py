@@ -29,6 +29,11 @@ Readings taken where the paper leaves a choice (each is restated where used):
   * Total order for selection: score descending, then index ascending; -0 == +0;
     NaN ranks below every number, -inf included.
   * Scores are stored, and the selection is decided, in float32.
+  * Head-wise budgets (Appendix "Orthogonality to Other Methods", head-wise budget
+    allocation): KV heads evict independently, so each may have a budget of its own;
+    the caches of the heads then differ in length, and a head's positions are counted
+    within its own cache (slot i of head m sits at position i, chunk token t at
+    n_c[m] + t).
 
 Parity pins (tests/test_oracle_*.py): brute-force dense masked attention written
 with Python loops, a library SDPA for the never-evicting case, sliding-window
@@ -123,14 +128,18 @@ def select_keep(scores: np.ndarray, budget: int, n_stab: int, n_pin: int = 0) ->
 # ----------------------------------------------------------------------------
 
 class LocretLayerOracle:
-    """State = per-KV-head K, V (un-rotated), true scores and original token positions."""
+    """State = per-KV-head K, V (un-rotated), true scores and original token positions.
+
+    budget: one int for every KV head, or a sequence of h_kv ints (head-wise budgets)."""
 
     def __init__(self, h: int, h_kv: int, d: int, budget: int, W1, W2, rh_kv_expand: int = 0,
                  rope: bool = False, theta: float = 10000.0, scale: float | None = None, n_pin: int = 0):
         assert h % h_kv == 0
         self.n_pin = n_pin          # units at the start of the cache that are never evicted (Locret-Q)
         self.h, self.h_kv, self.d, self.g = h, h_kv, d, h // h_kv
-        self.budget = budget
+        self.budgets = [int(budget)] * h_kv if np.ndim(budget) == 0 else [int(x) for x in budget]
+        assert len(self.budgets) == h_kv
+        self.budget = max(self.budgets)
         self.W1 = np.asarray(W1, dtype=np.float64)
         self.W2 = np.asarray(W2, dtype=np.float64)
         self.rh_kv_expand = rh_kv_expand
@@ -148,7 +157,11 @@ class LocretLayerOracle:
 
     @property
     def n_c(self) -> int:
-        return self.K[0].shape[0]
+        """Cache length (with head-wise budgets: of the longest head)."""
+        return max(self.K[m].shape[0] for m in range(self.h_kv))
+
+    def n_c_of(self, m: int) -> int:
+        return self.K[m].shape[0]
 
     # -- step 1: Eq. 1 over [cache ; chunk], causal inside the chunk ---------------------------
     def attention(self, q, k, v, rows=None) -> np.ndarray:
@@ -158,11 +171,11 @@ class LocretLayerOracle:
         k = np.asarray(k, dtype=np.float64)
         v = np.asarray(v, dtype=np.float64)
         T = q.shape[0]
-        n_c = self.n_c
         out = np.full((T, self.h, self.d), np.nan)
         ts = np.arange(T) if rows is None else np.asarray(rows)
         for j in range(self.h):
             m = j // self.g
+            n_c = self.n_c_of(m)
             keys = np.concatenate([self.K[m], k[:, m, :]], axis=0)       # [n_c + T][d]
             vals = np.concatenate([self.V[m], v[:, m, :]], axis=0)
             qj = q[ts, j, :]
@@ -186,7 +199,8 @@ class LocretLayerOracle:
     # -- steps 3-5 ----------------------------------------------------------------------------
     def evict_compact(self, scores, k, v, n_stab: int, evict: bool = True) -> np.ndarray:
         """Append the chunk (scores [h_kv][T] float32) and reduce to the budget.
-        Returns kept indices [h_kv][n_keep] in the concatenated index space."""
+        Returns kept indices [h_kv][n_keep] in the concatenated index space (a list of h_kv arrays
+        when head-wise budgets make the rows differ in length)."""
         k = np.asarray(k, dtype=np.float64)
         v = np.asarray(v, dtype=np.float64)
         scores = np.asarray(scores, dtype=np.float32)
@@ -198,12 +212,14 @@ class LocretLayerOracle:
             Sc = np.concatenate([self.S[m], scores[m]])
             Pc = np.concatenate([self.P[m], self.seen + np.arange(T, dtype=np.int64)])
             if evict:
-                idx = select_keep(Sc, self.budget, n_stab, self.n_pin)
+                idx = select_keep(Sc, self.budgets[m], n_stab, self.n_pin)
             else:
                 idx = np.arange(Sc.shape[0], dtype=np.int64)
             self.K[m], self.V[m], self.S[m], self.P[m] = Kc[idx], Vc[idx], Sc[idx], Pc[idx]
             kept_all.append(idx)
         self.seen += T
+        if len({len(x) for x in kept_all}) > 1:
+            return kept_all
         return np.stack(kept_all)
 
     # -- the whole step -----------------------------------------------------------------------

@@ -15,8 +15,9 @@ def _stream(w):
     return q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), W1, W2
 
 
-def _run(w, q, k, v, W1, W2, chunk_sizes=None):
-    o = LocretLayerOracle(w.h, w.h_kv, w.d, w.b, W1, W2, w.rh_kv_expand, w.rope, w.theta)
+def _run(w, q, k, v, W1, W2, chunk_sizes=None, budgets=None):
+    o = LocretLayerOracle(w.h, w.h_kv, w.d, w.b if budgets is None else budgets, W1, W2, w.rh_kv_expand,
+                          w.rope, w.theta)
     outs, kept_before, bounds = [], [], []
     lo = 0
     sizes = chunk_sizes or [w.B] * w.n_chunks
@@ -47,6 +48,24 @@ def test_step_by_step_equals_dense_masked_bruteforce(kw):
     w = synth.tiny(**kw)
     q, k, v, W1, W2 = _stream(w)
     got, kept_before, bounds, _ = _run(w, q, k, v, W1, W2)
+    want = np.array(bf.dense_masked_attention(q.tolist(), k.tolist(), v.tolist(), bounds, kept_before,
+                                              w.g, w.rope, w.theta))
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("kw,budgets", [
+    (dict(), [24, 9]),                                         # GQA, rope: positions counted per head
+    (dict(rope=False), [7, 30]),
+    (dict(h=3, h_kv=3, N=70, B=9, b=20, n_s=5), [20, 5, 11]),  # one head holds stabilizers only
+    (dict(h=4, h_kv=2, N=60, B=8, b=18, n_s=12), [18, 13]),    # n_s > B
+])
+def test_head_wise_budgets_equal_dense_masked_bruteforce(kw, budgets):
+    """Heads with budgets of their own hold caches of different lengths; the brute force rebuilds every
+    query's visible set, and each head's positions, from that head's kept list alone."""
+    w = synth.tiny(**kw)
+    q, k, v, W1, W2 = _stream(w)
+    got, kept_before, bounds, o = _run(w, q, k, v, W1, W2, budgets=budgets)
+    assert [o.n_c_of(m) for m in range(w.h_kv)] == [min(w.N, b) for b in budgets]
     want = np.array(bf.dense_masked_attention(q.tolist(), k.tolist(), v.tolist(), bounds, kept_before,
                                               w.g, w.rope, w.theta))
     np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)

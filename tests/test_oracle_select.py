@@ -150,6 +150,48 @@ def test_heads_evict_independently():
         assert o.P[m].tolist() == bf.closed_form_kept(scores[m], N, b, n_s)
 
 
+# ---- head-wise budgets (Appendix "Orthogonality to Other Methods": heads evict independently, so each
+# may have a budget of its own) ----------------------------------------------------------------------
+@pytest.mark.parametrize("budgets,n_s,n_pin", [
+    ([20, 7, 33], 4, 0),
+    ([12, 40, 12, 25], 12, 0),       # n_s equals the smallest budget: that head is a sliding window
+    ([200, 9, 30], 3, 0),            # one head never fills its budget
+    ([18, 9, 30], 3, 5),             # with a pinned prefix
+])
+def test_head_wise_budgets_match_closed_form_per_head(budgets, n_s, n_pin):
+    rng = np.random.default_rng(sum(budgets))
+    h_kv, N, B = len(budgets), 110, 12
+    scores = np.round(rng.standard_normal((h_kv, N)).astype(np.float32) * 2) / 2
+    o = LocretLayerOracle(h_kv, h_kv, 1, budgets, np.zeros((3 * h_kv, 1)), np.zeros((1, h_kv)), n_pin=n_pin)
+    prev = [[] for _ in range(h_kv)]
+    for lo in range(0, N, B):
+        hi = min(N, lo + B)
+        kv = np.arange(lo, hi, dtype=np.float64)[:, None, None] * np.ones((1, h_kv, 1))
+        kept = o.evict_compact(scores[:, lo:hi], kv, -kv, n_s)
+        for m in range(h_kv):
+            want = bf.closed_form_kept(scores[m], hi, budgets[m], n_s, n_pin)
+            assert o.P[m].tolist() == want
+            assert len(want) == min(hi, budgets[m])                     # every head within its own budget
+            cat = prev[m] + list(range(lo, hi))
+            assert [cat[i] for i in kept[m]] == want                    # indices in the head's own space
+            assert o.K[m][:, 0].tolist() == want and (o.V[m] == -o.K[m]).all()
+            np.testing.assert_array_equal(o.S[m], scores[m][want])
+            prev[m] = want
+    assert o.n_c == min(N, max(budgets)) and [o.n_c_of(m) for m in range(h_kv)] == [min(N, b) for b in budgets]
+
+
+def test_equal_head_budgets_are_the_single_budget():
+    rng = np.random.default_rng(3)
+    scores = rng.standard_normal((2, 60)).astype(np.float32)
+    a = LocretLayerOracle(2, 2, 1, 14, np.zeros((6, 1)), np.zeros((1, 2)))
+    b = LocretLayerOracle(2, 2, 1, [14, 14], np.zeros((6, 1)), np.zeros((1, 2)))
+    for lo in range(0, 60, 10):
+        kv = np.zeros((10, 2, 1))
+        ka = a.evict_compact(scores[:, lo:lo + 10], kv, kv, 3)
+        kb = b.evict_compact(scores[:, lo:lo + 10], kv, kv, 3)
+        np.testing.assert_array_equal(ka, kb)
+
+
 # ---- pinned prefix (Locret-Q: the query sits at the start of the sequence and is never evicted) -------
 PIN_HAND = [
     # scores, budget, n_stab, n_pin, expected kept indices (written out by hand)
