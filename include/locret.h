@@ -97,6 +97,20 @@ int locret_set_weights(locret_ctx* ctx, const void* W1, const void* W2, void* st
  * call with n_stab + n_pin > budget returns LOCRET_EINVAL.  Default 0; locret_reset keeps it. */
 int locret_set_pinned_prefix(locret_ctx* ctx, int32_t n_pin);
 
+/* Head-wise budgets (appendix "Orthogonality to Other Methods", head-wise budget allocation: KV heads
+ * evict independently, so every head may be given a budget of its own, as PyramidKV-style allocators do).
+ * budgets: HOST array of n_kv_heads values, 1 <= budgets[m] <= config.budget (LOCRET_EINVAL), copied; NULL
+ * restores the single budget of the config.  Only on an empty cache (after locret_create or locret_reset;
+ * LOCRET_ESTATE otherwise) and for n_kv_heads <= LOCRET_MAX_HEAD_BUDGETS (LOCRET_ESHAPE).  From then on an
+ * evicting call keeps min(n_c[m] + T, budgets[m]) units of head m, so the heads' caches differ in length;
+ * head m's slot i sits at position i and its chunk token t at n_c[m] + t (keys and the queries of its
+ * group), the stabilizers and the pinned prefix are clamped to the head's own length, and an evicting call
+ * with n_stab + n_pin > min(budgets) returns LOCRET_EINVAL.  Rows of kept_idx_out keep the stride
+ * config.budget; row m holds min(n_c[m] + T, budgets[m]) entries in head m's own concatenated index space.
+ * locret_reset keeps the budgets.  Host-only. */
+#define LOCRET_MAX_HEAD_BUDGETS 64
+int locret_set_head_budgets(locret_ctx* ctx, const int32_t* budgets);
+
 /* Empties the cache (n_c = 0, tokens seen = 0).  Host-only. */
 int locret_reset(locret_ctx* ctx);
 
@@ -144,8 +158,11 @@ int locret_evict_compact(locret_ctx* ctx, const float* chunk_scores, const void*
                          const void* v_chunk, int32_t T, int32_t n_stab, int32_t* kept_idx_out,
                          void* stream);
 
-/* Units currently in the cache per KV head (same for every head), and tokens seen so far. */
+/* Units currently in the cache per KV head (the same for every head; with head-wise budgets the longest
+ * head's), and tokens seen so far.  locret_cache_lens writes every head's length to lens (HOST,
+ * n_kv_heads values). */
 int32_t locret_cache_len(const locret_ctx* ctx);
+int locret_cache_lens(const locret_ctx* ctx, int32_t* lens);
 int64_t locret_tokens_seen(const locret_ctx* ctx);
 
 /* Device pointers into the workspace for the live cache copy: K, V [n_kv_heads][row_stride][head_dim]

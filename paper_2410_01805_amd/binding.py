@@ -24,6 +24,7 @@ EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_set_pinned_prefix", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
     "locret_destroy", "locret_strerror", "locret_profile_mode", "locret_profile_enable", "locret_profile_read",
+    "locret_set_head_budgets", "locret_cache_lens",
 ]
 LOCRET_PROF_STAGES = 5
 PROF_STAGE_NAMES = ("append", "attention", "retaining_head", "select", "compact")
@@ -63,6 +64,10 @@ def _load() -> C.CDLL:
     lib.locret_profile_mode.argtypes = [vp, i32]
     lib.locret_set_pinned_prefix.restype = C.c_int
     lib.locret_set_pinned_prefix.argtypes = [vp, i32]
+    lib.locret_set_head_budgets.restype = C.c_int
+    lib.locret_set_head_budgets.argtypes = [vp, C.POINTER(i32)]
+    lib.locret_cache_lens.restype = C.c_int
+    lib.locret_cache_lens.argtypes = [vp, C.POINTER(i32)]
     lib.locret_cache_len.restype = C.c_int32
     lib.locret_cache_len.argtypes = [vp]
     lib.locret_tokens_seen.restype = C.c_int64
@@ -153,6 +158,18 @@ def locret_profile_mode(ctx, mode: int) -> None:
 
 def locret_set_pinned_prefix(ctx, n_pin: int) -> None:
     _check(lib.locret_set_pinned_prefix(ctx, n_pin), "locret_set_pinned_prefix")
+
+
+def locret_set_head_budgets(ctx, budgets) -> None:
+    """budgets: a sequence of n_kv_heads ints (host), or None for the config's single budget."""
+    arr = None if budgets is None else (C.c_int32 * len(budgets))(*[int(b) for b in budgets])
+    _check(lib.locret_set_head_budgets(ctx, arr), "locret_set_head_budgets")
+
+
+def locret_cache_lens(ctx, n_kv_heads: int) -> list:
+    arr = (C.c_int32 * n_kv_heads)()
+    _check(lib.locret_cache_lens(ctx, arr), "locret_cache_lens")
+    return list(arr)
 
 
 def locret_decode_step(ctx, q, k, v, with_score, attn_out, scores_out=None, stream=None) -> None:
@@ -248,6 +265,15 @@ class LocretLayer:
     def set_pinned_prefix(self, n_pin: int) -> None:
         locret_set_pinned_prefix(self.ctx, n_pin)
 
+    def set_head_budgets(self, budgets) -> None:
+        if budgets is not None and len(budgets) != self.cfg.n_kv_heads:
+            raise LocretError(LOCRET_EINVAL, "locret_set_head_budgets")
+        locret_set_head_budgets(self.ctx, budgets)
+
+    @property
+    def cache_lens(self) -> list:
+        return locret_cache_lens(self.ctx, self.cfg.n_kv_heads)
+
     def decode_step(self, q, k, v, with_score=False):
         """One generated token: q [1][h][d], k, v [1][h_kv][d] -> (attn_out [1][h][d], scores [h_kv] or None)."""
         import torch
@@ -268,7 +294,8 @@ class LocretLayer:
 
     def cache_tensors(self):
         """Copies of the live cache (K, V in storage dtype, score float32, orig_pos int32), each
-        [h_kv][len][...], taken from the workspace through locret_cache_view."""
+        [h_kv][len][...], taken from the workspace through locret_cache_view (with head-wise budgets
+        len is the longest head's: row m is meaningful up to cache_lens[m])."""
         import torch
         view = locret_cache_view(self.ctx)
         base = self.workspace.data_ptr()

@@ -94,6 +94,22 @@ struct locret_ctx {
   int64_t seen;     // tokens appended so far
   int have_weights;
   int n_pin;        // units at the start of the cache that no call evicts (Locret-Q's query prefix)
+  // head-wise budgets: n_c is then the longest head's length
+  int ragged;
+  int b_h[MAX_HEAD_BUDGETS];     // budget of every KV head
+  int n_c_h[MAX_HEAD_BUDGETS];   // units of every KV head in the live copy
+  // the heads' lengths plus `add` in the form the launchers take, or NULL when all heads hold n_c units
+  const HeadLens* lens(HeadLens* tmp, int add = 0) const {
+    if (!ragged) return nullptr;
+    tmp->ragged = 1;
+    for (int m = 0; m < D.h_kv; ++m) tmp->v[m] = n_c_h[m] + add;
+    return tmp;
+  }
+  int min_budget() const {
+    int b = cfg.budget;
+    if (ragged) for (int m = 0; m < D.h_kv; ++m) b = b_h[m] < b ? b_h[m] : b;
+    return b;
+  }
   float scale;
   int mfma_attn, mfma_score;
   // Selection and compaction depend on the scores only, and compaction writes the other cache copy,
@@ -141,6 +157,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   if (!c) return LOCRET_ENOMEM;
   c->cur = 0; c->n_c = 0; c->seen = 0; c->have_weights = 0; c->prof_max = 0; c->prof_calls = 0;
   c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->overlap = 0; c->n_pin = 0; c->prof_mode = 0;
+  c->ragged = 0;
   c->cfg = *cfg;
   fill_dims(cfg, &c->D);
   make_layout(cfg, c->D, &c->L);
@@ -196,16 +213,30 @@ int locret_set_pinned_prefix(locret_ctx* c, int32_t n_pin) {
   return LOCRET_OK;
 }
 
+int locret_set_head_budgets(locret_ctx* c, const int32_t* budgets) {
+  if (!c) return LOCRET_EINVAL;
+  if (c->n_c != 0) return LOCRET_ESTATE;
+  if (!budgets) { c->ragged = 0; return LOCRET_OK; }
+  if (c->D.h_kv > MAX_HEAD_BUDGETS) return LOCRET_ESHAPE;
+  for (int m = 0; m < c->D.h_kv; ++m)
+    if (budgets[m] < 1 || budgets[m] > c->cfg.budget) return LOCRET_EINVAL;
+  for (int m = 0; m < c->D.h_kv; ++m) { c->b_h[m] = budgets[m]; c->n_c_h[m] = 0; }
+  c->ragged = 1;
+  return LOCRET_OK;
+}
+
 int locret_reset(locret_ctx* c) {
   if (!c) return LOCRET_EINVAL;
   c->n_c = 0;
   c->seen = 0;
+  for (int m = 0; m < MAX_HEAD_BUDGETS; ++m) c->n_c_h[m] = 0;
   return LOCRET_OK;
 }
 
 // reduce = false: only the partial scores are formed (ws + L.part, *n_parts of them); the caller sums them
 static void run_score(locret_ctx* c, const void* q, const void* k, const void* v, int T, float* S_dst, int n_c,
                       float* out, hipStream_t st, bool reduce = true, int* n_parts = nullptr) {
+  HeadLens hl_tmp;
   float* part = (float*)(c->ws + c->L.part);
   int parts;
   if (c->mfma_score) {
@@ -216,7 +247,7 @@ static void run_score(locret_ctx* c, const void* q, const void* k, const void* v
     parts = score_parts_simple(c->D);
   }
   if (n_parts) *n_parts = parts;
-  if (reduce) launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st);
+  if (reduce) launch_score_reduce(part, parts, T, c->D.h_kv, T, S_dst, c->D.cap, n_c, out, st, c->lens(&hl_tmp));
 }
 
 // the selection over the live copy's rows [0, L)
@@ -226,8 +257,20 @@ static SelectArgs select_args(locret_ctx* c, int L, int n_stab, int32_t* kept_id
   const int ns = n_stab < L ? n_stab : L;
   const int npin = c->n_pin < L - ns ? c->n_pin : L - ns;     // the prefix covers what the stabilizers leave
   CacheBuf A = c->buf(c->cur);
-  return SelectArgs{A.S, c->D.cap, L, n_keep, ns, npin, (int32_t*)(c->ws + c->L.kept), b, kept_idx_out, b,
-                    nullptr, 0, 0, 0, 0, 0, nullptr, nullptr};
+  SelectArgs a = {A.S, c->D.cap, L, n_keep, ns, npin, (int32_t*)(c->ws + c->L.kept), b, kept_idx_out, b,
+                  nullptr, 0, 0, 0, 0, nullptr, nullptr};
+  a.L_h.ragged = a.keep_h.ragged = c->ragged;
+  if (c->ragged) {
+    // L is the longest head's length (it sizes the launch); every head clamps n_stab and n_pin to its own
+    a.n_keep = 0;
+    for (int m = 0; m < c->D.h_kv; ++m) {
+      const int Lm = c->n_c_h[m] + (L - c->n_c);
+      a.L_h.v[m] = Lm;
+      a.keep_h.v[m] = Lm < c->b_h[m] ? Lm : c->b_h[m];
+      a.n_keep = a.keep_h.v[m] > a.n_keep ? a.keep_h.v[m] : a.n_keep;
+    }
+  }
+  return a;
 }
 
 // select + compact on the live copy, whose rows [0, L) are filled; updates the host bookkeeping.
@@ -237,17 +280,31 @@ static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, h
   const SelectArgs a = select_args(c, L, n_stab, kept_idx_out);
   CacheBuf A = c->buf(c->cur);
   c->mark(3, 0, st);
-  if (!select_done)
-    launch_select(a.S, a.cap, c->D.h_kv, a.L, a.n_keep, a.n_stab, a.n_pin, a.kept, a.kept_stride, a.kept2, a.stride2, st);
+  if (!select_done) launch_select(a, c->D.h_kv, st);
   c->mark(3, 1, st);
   c->mark(4, 0, st);
-  if (L > b) {
+  // the other copy becomes the live one as soon as one head is over its budget; the heads that are not
+  // are then copied as they are (their kept lists are 0, 1, 2, ...)
+  bool over = L > b;
+  if (c->ragged) {
+    over = false;
+    for (int m = 0; m < c->D.h_kv; ++m) over = over || a.L_h.v[m] > c->b_h[m];
+  }
+  if (over) {
     CacheBuf B = c->buf(c->cur ^ 1);
-    launch_compact(c->D, A, B, a.kept, b, a.n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st);
+    launch_compact(c->D, A, B, a.kept, b, a.n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st,
+                   c->ragged ? &a.keep_h : nullptr);
     c->cur ^= 1;
   }
   c->mark(4, 1, st);
   c->n_c = a.n_keep;
+  if (c->ragged) for (int m = 0; m < c->D.h_kv; ++m) c->n_c_h[m] = a.keep_h.v[m];
+}
+
+// the cache grew by T units in every head and nothing was evicted
+static void grow(locret_ctx* c, int T) {
+  c->n_c += T;
+  if (c->ragged) for (int m = 0; m < c->D.h_kv; ++m) c->n_c_h[m] += T;
 }
 
 int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, int32_t n_stab,
@@ -255,7 +312,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
                          int32_t* kept_idx_out, void* stream) {
   if (!c || !q || !k || !v || !attn_out) return LOCRET_EINVAL;
   if (n_stab < 0 || n_stab > c->cfg.budget) return LOCRET_EINVAL;
-  if (evict && n_stab + c->n_pin > c->cfg.budget) return LOCRET_EINVAL;
+  if (evict && n_stab + c->n_pin > c->min_budget()) return LOCRET_EINVAL;
   if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(attn_out) || misaligned(scores_in) ||
       misaligned(scores_out) || misaligned(kept_idx_out))
@@ -270,8 +327,10 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
 
   // the head_dim-128 attention kernel rotates the queries itself: no rotated copy is written or read
   const bool fused_q = c->mfma_attn && attention_bf16_rotates_q(D);
+  HeadLens hl_tmp;
+  const HeadLens* hl = c->lens(&hl_tmp);      // per-head cache lengths before this chunk, or NULL
   c->mark(0, 0, st);
-  launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st);
+  launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st, false, hl);
   c->mark(0, 1, st);
   const void* qx = (D.rope && !fused_q) ? qr : q;
   const void* Kx = D.rope ? A.Kr : A.K;
@@ -284,12 +343,12 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
       LaunchTimer tm;
       tm.start = c->prof_event(1, 0);
       tm.stop = c->prof_event(1, 1);
-      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel);
+      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel, hl);
       return;
     }
     c->mark(1, 0, st);
-    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, LaunchTimer(), sel);
-    else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st);
+    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, LaunchTimer(), sel, hl);
+    else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, hl);
     c->mark(1, 1, st);
   };
   auto scores = [&](SelectArgs* fused) {
@@ -302,13 +361,12 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
       fused->n_parts = parts;
       fused->part_T = T;
       fused->h_kv = D.h_kv;
-      fused->red_n_c = n_c;
       fused->red_T = T;
       fused->S_w = A.S;
       fused->red_out = scores_out;
     } else {
       run_score(c, q, k, v, T, scores_in ? nullptr : A.S, n_c, scores_out, st);
-      if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, n_c, nullptr, st);
+      if (scores_in) launch_score_reduce(scores_in, 1, T, D.h_kv, T, A.S, D.cap, n_c, nullptr, st, hl);
     }
     c->mark(2, 1, st);
   };
@@ -341,7 +399,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     scores(nullptr);
     if (evict) run_evict(c, L, n_stab, kept_idx_out, st);
     else {
-      c->n_c = L;
+      grow(c, T);
       c->mark(3, 0, st); c->mark(3, 1, st); c->mark(4, 0, st); c->mark(4, 1, st);
     }
   }
@@ -361,11 +419,12 @@ int locret_decode_step(locret_ctx* c, const void* q, const void* k, const void* 
   CacheBuf A = c->buf(c->cur);
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   void* qr = D.rope ? c->ws + c->L.qr : nullptr;
-  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st, /*mark_unscored=*/!with_score);
+  HeadLens hl_tmp;
+  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st, /*mark_unscored=*/!with_score, c->lens(&hl_tmp));
   if (with_score) run_score(c, q, k, v, 1, A.S, c->n_c, scores_out, st);
   launch_decode_attention(D, D.rope ? qr : q, D.rope ? A.Kr : A.K, A.V, attn_out, c->n_c + 1, c->scale,
-                          (float*)(c->ws + c->L.dpart), st);
-  c->n_c += 1;
+                          (float*)(c->ws + c->L.dpart), st, c->lens(&hl_tmp, 1));
+  grow(c, 1);
   c->seen += 1;
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
 }
@@ -383,7 +442,7 @@ int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int
 int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k, const void* v, int32_t T,
                          int32_t n_stab, int32_t* kept_idx_out, void* stream) {
   if (!c || !chunk_scores || !k || !v) return LOCRET_EINVAL;
-  if (n_stab < 0 || n_stab + c->n_pin > c->cfg.budget) return LOCRET_EINVAL;
+  if (n_stab < 0 || n_stab + c->n_pin > c->min_budget()) return LOCRET_EINVAL;
   if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
   if (misaligned(chunk_scores) || misaligned(k) || misaligned(v) || misaligned(kept_idx_out)) return LOCRET_EALIGN;
   if (c->n_c + T > c->D.cap) return LOCRET_ESTATE;
@@ -391,14 +450,21 @@ int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k
   const Dims& D = c->D;
   CacheBuf A = c->buf(c->cur);
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
-  launch_append(D, nullptr, k, v, T, c->n_c, c->seen, A, nullptr, tab, st);
-  launch_score_reduce(chunk_scores, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st);
+  HeadLens hl_tmp;
+  const HeadLens* hl = c->lens(&hl_tmp);
+  launch_append(D, nullptr, k, v, T, c->n_c, c->seen, A, nullptr, tab, st, false, hl);
+  launch_score_reduce(chunk_scores, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st, hl);
   run_evict(c, c->n_c + T, n_stab, kept_idx_out, st);
   c->seen += T;
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
 }
 
 int32_t locret_cache_len(const locret_ctx* c) { return c ? c->n_c : LOCRET_EINVAL; }
+int locret_cache_lens(const locret_ctx* c, int32_t* lens) {
+  if (!c || !lens) return LOCRET_EINVAL;
+  for (int m = 0; m < c->D.h_kv; ++m) lens[m] = c->ragged ? c->n_c_h[m] : c->n_c;
+  return LOCRET_OK;
+}
 int64_t locret_tokens_seen(const locret_ctx* c) { return c ? c->seen : (int64_t)LOCRET_EINVAL; }
 
 int locret_cache_view(const locret_ctx* c, const void** K, const void** V, const float** score,

@@ -41,8 +41,8 @@ template <int D, int QB, int NW, int WPE>
 __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab,
                                                              const bf16_t* __restrict__ Kx, const bf16_t* __restrict__ V,
                                                              bf16_t* __restrict__ out,
-                                                             int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                             int hpw, int n_hgroups, int n_ttiles) {
+                                                             int Tn, int h, int g, int cap, int n_c_common, float c_log2,
+                                                             int hpw, int n_hgroups, int n_ttiles, HeadLens n_c_h) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
   constexpr int NDB = D / 32;          // 32-row blocks of O^T
   constexpr int KCH = D / 8;           // 16-byte chunks per K row
@@ -76,6 +76,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;     // query head of this wavefront
   const int m = (hgroup * hpw) / g;            // KV head: the same for all four wavefronts (blockIdx only)
+  const int n_c = __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common));   // this head's cache length
   const int tw0 = t0 + (wave % wph) * 32 * QB; // first token of this wavefront
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;      // slots the workgroup stages
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
 
 template <int D, int QB, int NW, int WPE>
 static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T,
-                        int n_c, float scale, hipStream_t st) {
+                        int n_c, float scale, hipStream_t st, const HeadLens& hl) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
   const int wph = NW / hpw;
@@ -401,7 +402,7 @@ static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const flo
   hipExtLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop,
                         0, (const bf16_t*)q, tab,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
-                     n_hgroups, n_ttiles);
+                     n_hgroups, n_ttiles, hl);
 }
 
 // LOCRET_ATTN_VARIANT selects a kernel for experiments: default "pp" (direct-to-LDS staging with the two
@@ -439,22 +440,24 @@ bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
 }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                           float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel) {
+                           float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel,
+                           const HeadLens* n_c_h) {
   const int v = attn_variant();
-  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel)) return;
-  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
-  if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st)) return;
+  const HeadLens hl = head_lens_or_common(n_c_h);
+  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h)) return;
+  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
+  if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
 #define LOCRET_CASE(DD)                                                                           \
   case DD:                                                                                        \
-    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);        \
-    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);   \
-    else attn_launch<DD, 1, 8, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st);               \
+    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl);    \
+    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl); \
+    else attn_launch<DD, 1, 8, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl);           \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)
     LOCRET_CASE(96)
     LOCRET_CASE(128)
-    default: launch_attention_simple(Dm, q, Kx, V, out, T, n_c, scale, st);
+    default: launch_attention_simple(Dm, q, Kx, V, out, T, n_c, scale, st, n_c_h);
   }
 #undef LOCRET_CASE
 }

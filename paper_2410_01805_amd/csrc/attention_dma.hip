@@ -54,8 +54,8 @@ constexpr int DM_STAGE_B = 2 * DM_TILE_B;      // K then V
 template <int NW, int NSTAGE>
 __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                               const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
-                                                              int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                              int hpw, int n_hgroups, int n_ttiles) {
+                                                              int Tn, int h, int g, int cap, int n_c_common, float c_log2,
+                                                              int hpw, int n_hgroups, int n_ttiles, HeadLens n_c_h) {
   constexpr int D = DM_D;
   constexpr int NKS = D / 16;
   constexpr int NDB = D / 32;
@@ -84,6 +84,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;
   const int m = (hgroup * hpw) / g;
+  const int n_c = __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common));   // this KV head's cache length
   const int tw0 = t0 + (wave % wph) * 32;
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_dma_kernel(const bf16_t* __re
 
 template <int NW, int NSTAGE>
 static void dma_launch(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out, int T, int n_c,
-                       float scale, hipStream_t st) {
+                       float scale, hipStream_t st, const HeadLens& hl) {
   const int g = Dm.g;
   const int hpw = (NW == 8 && g % 8 == 0) ? 8 : (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
   const int wph = NW / hpw;
@@ -374,17 +375,18 @@ static void dma_launch(const Dims& Dm, LaunchTimer tm, const void* q, const floa
   const float c_log2 = scale * 1.4426950408889634f;
   hipExtLaunchKernelGGL((attn_dma_kernel<NW, NSTAGE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
                      (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
-                     c_log2, hpw, n_hgroups, n_ttiles);
+                     c_log2, hpw, n_hgroups, n_ttiles, hl);
 }
 
 // `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
 // variant 0: 8 wavefronts, 4-stage ring (one workgroup per CU); 1: 4 wavefronts, 2-stage ring (two per CU)
 bool launch_attention_bf16_dma(const Dims& Dm, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                               int T, int n_c, float scale, hipStream_t st) {
+                               int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h) {
+  const HeadLens hl = head_lens_or_common(n_c_h);
   if (Dm.d != DM_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
-  if (variant == 1) dma_launch<4, 2>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st);
-  else dma_launch<8, 4>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st);
+  if (variant == 1) dma_launch<4, 2>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st, hl);
+  else dma_launch<8, 4>(Dm, tm, q, tab, Kx, V, out, T, n_c, scale, st, hl);
   return true;
 }
 

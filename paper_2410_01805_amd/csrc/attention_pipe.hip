@@ -27,8 +27,8 @@ namespace locret {
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_pipe_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kx,
                                                            const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
-                                                           int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                           int hpw, int n_hgroups, int n_ttiles) {
+                                                           int Tn, int h, int g, int cap, int n_c_common, float c_log2,
+                                                           int hpw, int n_hgroups, int n_ttiles, HeadLens n_c_h) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
   constexpr int NDB = D / 32;          // 32-row blocks of O^T
   constexpr int KCH = D / 8;           // 16-byte chunks per K row
@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256, 2) void attn_pipe_kernel(const bf16_t* __restr
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;     // query head of this wavefront
   const int m = (hgroup * hpw) / g;            // KV head: the same for all four wavefronts
+  const int n_c = __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common));   // this KV head's cache length
   const int tw0 = t0 + (wave % wph) * 32;      // first token of this wavefront
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;      // slots the workgroup stages
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(256, 2) void attn_pipe_kernel(const bf16_t* __restr
 
 template <int D>
 static void pipe_launch(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
-                        float scale, hipStream_t st) {
+                        float scale, hipStream_t st, const HeadLens& hl) {
   const int g = Dm.g;
   const int hpw = (g % 4 == 0) ? 4 : (g % 2 == 0) ? 2 : 1;
   const int wph = 4 / hpw;
@@ -350,15 +351,16 @@ static void pipe_launch(const Dims& Dm, const void* q, const void* Kx, const voi
   const float c_log2 = scale * 1.4426950408889634f;
   hipLaunchKernelGGL((attn_pipe_kernel<D>), dim3(n_hgroups * n_ttiles), dim3(256), 0, st, (const bf16_t*)q,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
-                     n_hgroups, n_ttiles);
+                     n_hgroups, n_ttiles, hl);
 }
 
 bool launch_attention_bf16_pipe(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T,
-                                int n_c, float scale, hipStream_t st) {
+                                int n_c, float scale, hipStream_t st, const HeadLens* n_c_h) {
+  const HeadLens hl = head_lens_or_common(n_c_h);
   switch (Dm.d) {
-    case 64: pipe_launch<64>(Dm, q, Kx, V, out, T, n_c, scale, st); return true;
-    case 96: pipe_launch<96>(Dm, q, Kx, V, out, T, n_c, scale, st); return true;
-    case 128: pipe_launch<128>(Dm, q, Kx, V, out, T, n_c, scale, st); return true;
+    case 64: pipe_launch<64>(Dm, q, Kx, V, out, T, n_c, scale, st, hl); return true;
+    case 96: pipe_launch<96>(Dm, q, Kx, V, out, T, n_c, scale, st, hl); return true;
+    case 128: pipe_launch<128>(Dm, q, Kx, V, out, T, n_c, scale, st, hl); return true;
     default: return false;
   }
 }

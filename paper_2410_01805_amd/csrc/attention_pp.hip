@@ -60,8 +60,9 @@ constexpr int PP_SEL_MAXR = 48;                // keys per thread of a selection
 
 __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
-                                                             int Tn, int h, int g, int cap, int n_c, float c_log2,
-                                                             int hpw, int n_hgroups, int n_ttiles, SelectArgs sel, int n_sel) {
+                                                             int Tn, int h, int g, int cap, int n_c_common, float c_log2,
+                                                             int hpw, int n_hgroups, int n_ttiles, SelectArgs sel, int n_sel,
+                                                             HeadLens n_c_h) {
   constexpr int NW = PP_NW;
   constexpr int D = PP_D;
   constexpr int NKS = D / 16;
@@ -98,6 +99,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;
   const int m = (hgroup * hpw) / g;
+  const int n_c = __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common));   // this KV head's cache length
   const int tw0 = t0 + (wave % wph) * 32;
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;
@@ -414,7 +416,8 @@ bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
 
 // `sel` non-null (and attention_pp_fuses_select true): the launch also performs that selection.
 bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                              int T, int n_c, float scale, hipStream_t st, const SelectArgs* sel) {
+                              int T, int n_c, float scale, hipStream_t st, const SelectArgs* sel,
+                              const HeadLens* n_c_h) {
   if (Dm.d != PP_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
   constexpr int NW = PP_NW;
@@ -429,7 +432,7 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
   const SelectArgs sa = sel ? *sel : SelectArgs{};
   hipExtLaunchKernelGGL(attn_pp_kernel, dim3(n_sel + n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
                         (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
-                        c_log2, hpw, n_hgroups, n_ttiles, sa, n_sel);
+                        c_log2, hpw, n_hgroups, n_ttiles, sa, n_sel, head_lens_or_common(n_c_h));
   return true;
 }
 

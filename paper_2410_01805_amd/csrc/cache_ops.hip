@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
                                                      T* __restrict__ Vc, T* __restrict__ Krc,
                                                      int32_t* __restrict__ Pc, T* __restrict__ qr,
                                                      const float2* __restrict__ tab, int rope, int q_rows,
-                                                     float* __restrict__ S_unscored) {
+                                                     float* __restrict__ S_unscored, HeadLens n_c_h) {
   constexpr int VEC = Vec16<T>::N;
   const int half = d / 2;
   const int tpr = half / VEC;
@@ -109,7 +109,8 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
     V16 lo, hi, olo, ohi;
     lo.raw = *(const decltype(lo.raw)*)(src + off);
     hi.raw = *(const decltype(hi.raw)*)(src + half + off);
-    rotate_pairs<T>(lo, hi, olo, ohi, tab + (int64_t)(n_c + t) * half + off);
+    const int n_c_q = head_len(n_c_h, r / (h / h_kv), n_c);   // a query sits behind its own KV head's cache
+    rotate_pairs<T>(lo, hi, olo, ohi, tab + (int64_t)(n_c_q + t) * half + off);
     T* dst = qr + ((int64_t)t * h + r) * d;
     *(decltype(lo.raw)*)(dst + off) = olo.raw;
     *(decltype(lo.raw)*)(dst + half + off) = ohi.raw;
@@ -118,6 +119,7 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
   r -= q_rows;
   const bool is_k = r < h_kv;
   int m = is_k ? r : r - h_kv;
+  n_c = head_len(n_c_h, m, n_c);
   const T* src = (is_k ? k : v) + ((int64_t)t * h_kv + m) * d;
   V16 lo, hi;
   lo.raw = *(const decltype(lo.raw)*)(src + off);
@@ -141,8 +143,10 @@ __global__ __launch_bounds__(256) void append_kernel(const T* __restrict__ q, co
 }
 
 void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c, int64_t seen,
-                   const CacheBuf& c, void* qr, const float2* tab, hipStream_t st, bool mark_unscored) {
+                   const CacheBuf& c, void* qr, const float2* tab, hipStream_t st, bool mark_unscored,
+                   const HeadLens* n_c_h) {
   float* Su = mark_unscored ? c.S : nullptr;
+  const HeadLens hl = head_lens_or_common(n_c_h);
   const int vec = D.bf16 ? 8 : 4;
   const int tpr = (D.d / 2) / vec;
   const int q_rows = (D.rope && q != nullptr) ? D.h : 0;
@@ -151,11 +155,11 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
   if (D.bf16)
     hipLaunchKernelGGL(append_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (bf16_t*)c.K, (bf16_t*)c.V,
-                       (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows, Su);
+                       (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows, Su, hl);
   else
     hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
                        (const float*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (float*)c.K, (float*)c.V,
-                       (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows, Su);
+                       (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows, Su, hl);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -176,14 +180,16 @@ __device__ __forceinline__ void nt_store16(void* p, R r) {
   __builtin_nontemporal_store(__builtin_bit_cast(nt_u32x4, r), (nt_u32x4*)p);
 }
 
-template <typename T, int HB>
+// RAGGED: head m has keep_h.v[m] rows (head-wise budgets); rows beyond that are neither read nor written.
+template <typename T, int HB, bool RAGGED>
 __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                       const float* __restrict__ Ss, const int32_t* __restrict__ Ps,
                                                       T* __restrict__ Kd, T* __restrict__ Vd, T* __restrict__ Krd,
                                                       float* __restrict__ Sd, int32_t* __restrict__ Pd,
                                                       const int32_t* __restrict__ kept, int kept_stride,
                                                       int n_keep, int h_kv, int d, int cap,
-                                                      const float2* __restrict__ tab, int rope, int hpb) {
+                                                      const float2* __restrict__ tab, int rope, int hpb,
+                                                      HeadLens keep_h) {
   constexpr int VEC = Vec16<T>::N;
   typedef Vec16<T> V16;
   typedef decltype(V16().raw) raw_t;
@@ -207,7 +213,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
 #pragma unroll
     for (int u = 0; u < HB; ++u) {
       const int m = min(m0 + u, m_hi - 1);          // spare iterations repeat the last head (stores are skipped)
-      src[u] = kept[(int64_t)m * kept_stride + r];
+      if (RAGGED) src[u] = r < keep_h.v[m] ? kept[(int64_t)m * kept_stride + r] : 0;   // row 0: a valid address
+      else src[u] = kept[(int64_t)m * kept_stride + r];
     }
 #pragma unroll
     for (int u = 0; u < HB; ++u) {
@@ -222,6 +229,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
     for (int u = 0; u < HB; ++u) {
       const int m = m0 + u;
       if (m >= m_hi) break;
+      if (RAGGED && r >= keep_h.v[m]) continue;
       const int64_t drow = ((int64_t)m * cap + r) * d;
       nt_store16(Kd + drow + off, klo[u].raw);
       nt_store16(Kd + drow + half + off, khi[u].raw);
@@ -247,7 +255,8 @@ __global__ __launch_bounds__(256) void compact_kernel(const T* __restrict__ Ks, 
 }
 
 void launch_compact(const Dims& D, const CacheBuf& s, const CacheBuf& t, const int32_t* kept, int kept_stride,
-                    int n_keep, const float2* tab, hipStream_t st) {
+                    int n_keep, const float2* tab, hipStream_t st, const HeadLens* keep_h) {
+  const HeadLens hl = head_lens_or_common(keep_h);
   const int vec = D.bf16 ? 8 : 4;
   const int tpr = (D.d / 2) / vec;
   int64_t threads = (int64_t)n_keep * tpr;
@@ -260,14 +269,13 @@ void launch_compact(const Dims& D, const CacheBuf& s, const CacheBuf& t, const i
   while (hpb > 2 && (int64_t)gx * ((D.h_kv + hpb - 1) / hpb) < 768) hpb = (hpb + 1) / 2;
   dim3 grid(gx, (unsigned)((D.h_kv + hpb - 1) / hpb));
   // two heads per batch: enough loads in flight per thread while registers still allow many wavefronts
-  if (D.bf16)
-    hipLaunchKernelGGL((compact_kernel<bf16_t, 2>), grid, dim3(256), 0, st, (const bf16_t*)s.K, (const bf16_t*)s.V,
-                       s.S, s.P, (bf16_t*)t.K, (bf16_t*)t.V, (bf16_t*)t.Kr, t.S, t.P, kept, kept_stride, n_keep,
-                       D.h_kv, D.d, D.cap, tab, D.rope, hpb);
-  else
-    hipLaunchKernelGGL((compact_kernel<float, 2>), grid, dim3(256), 0, st, (const float*)s.K, (const float*)s.V, s.S,
-                       s.P, (float*)t.K, (float*)t.V, (float*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv, D.d,
-                       D.cap, tab, D.rope, hpb);
+#define LOCRET_COMPACT(TT, RG)                                                                                   \
+  hipLaunchKernelGGL((compact_kernel<TT, 2, RG>), grid, dim3(256), 0, st, (const TT*)s.K, (const TT*)s.V, s.S, s.P, \
+                     (TT*)t.K, (TT*)t.V, (TT*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv, D.d, D.cap, tab,   \
+                     D.rope, hpb, hl)
+  if (D.bf16) { if (hl.ragged) LOCRET_COMPACT(bf16_t, true); else LOCRET_COMPACT(bf16_t, false); }
+  else { if (hl.ragged) LOCRET_COMPACT(float, true); else LOCRET_COMPACT(float, false); }
+#undef LOCRET_COMPACT
 }
 
 }  // namespace locret

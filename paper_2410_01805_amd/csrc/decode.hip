@@ -27,8 +27,9 @@ template <> struct Pow2Ceil<1> { static constexpr int value = 1; };
 template <typename T, int D, int G>
 __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ Kx,
                                                                   const T* __restrict__ V, int g, int g0, int cap,
-                                                                  int n_keys, int keys_per_wg, float c_log2,
-                                                                  float* __restrict__ part, int n_splits) {
+                                                                  int n_keys_common, int keys_per_wg, float c_log2,
+                                                                  float* __restrict__ part, int n_splits,
+                                                                  HeadLens n_keys_h) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int LPR = D / VEC;                       // lanes that hold data of one row
   constexpr int LPRP = Pow2Ceil<LPR>::value;         // lanes reserved per row
@@ -43,6 +44,9 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPRP, grp = lane / LPRP;
   const bool act = sub < LPR;
+  // head-wise budgets: a head shorter than the longest leaves its last splits empty (k1 <= k0: no row is
+  // read, the partial carries max -inf and sum 0, which the merge weighs with 0)
+  const int n_keys = head_len(n_keys_h, m, n_keys_common);
   const int k0 = split * keys_per_wg;
   const int k1 = min(n_keys, k0 + keys_per_wg);
   const T* Kb = Kx + (int64_t)m * cap * D;
@@ -232,7 +236,7 @@ int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() -
 
 template <typename T, int DD>
 static void decode_launch(const Dims& D, const T* q, const T* Kx, const T* V, T* out, int n_keys, float scale,
-                          float* part, hipStream_t st) {
+                          float* part, hipStream_t st, const HeadLens& hl) {
   const int kpw = decode_keys_per_split();
   const int n_splits = (n_keys + kpw - 1) / kpw;
   const float c_log2 = scale * 1.4426950408889634f;
@@ -241,25 +245,26 @@ static void decode_launch(const Dims& D, const T* q, const T* Kx, const T* V, T*
     const int left = D.g - g0;
     if (left >= 3)
       hipLaunchKernelGGL((decode_attn_kernel<T, DD, 4>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits);
+                         kpw, c_log2, part, n_splits, hl);
     else if (left == 2)
       hipLaunchKernelGGL((decode_attn_kernel<T, DD, 2>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits);
+                         kpw, c_log2, part, n_splits, hl);
     else
       hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits);
+                         kpw, c_log2, part, n_splits, hl);
   }
   hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, part, n_splits, D.d, out);
 }
 
 void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
-                             float scale, float* part, hipStream_t st) {
+                             float scale, float* part, hipStream_t st, const HeadLens* n_keys_h) {
+  const HeadLens hl = head_lens_or_common(n_keys_h);
 #define LOCRET_DEC(DD)                                                                                              \
   case DD:                                                                                                          \
     if (D.bf16) decode_launch<bf16_t, DD>(D, (const bf16_t*)q, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out,  \
-                                          n_keys, scale, part, st);                                            \
+                                          n_keys, scale, part, st, hl);                                        \
     else decode_launch<float, DD>(D, (const float*)q, (const float*)Kx, (const float*)V, (float*)out, n_keys,      \
-                                  scale, part, st);                                                                 \
+                                  scale, part, st, hl);                                                             \
     break;
   switch (D.d) {
     LOCRET_DEC(16)

@@ -14,6 +14,21 @@ struct LaunchTimer {
   hipEvent_t stop = nullptr;
 };
 
+// Head-wise budgets (appendix "Orthogonality to Other Methods", head-wise budget allocation: KV heads evict
+// independently, so each may have its own budget): the heads' caches then differ in length.  Kernels take
+// this by value beside the common length; ragged == 0: every head has the common length.
+constexpr int MAX_HEAD_BUDGETS = 64;
+struct HeadLens {
+  int ragged;
+  int v[MAX_HEAD_BUDGETS];
+};
+__host__ __device__ inline int head_len(const HeadLens& hl, int m, int common) { return hl.ragged ? hl.v[m] : common; }
+inline HeadLens head_lens_or_common(const HeadLens* hl) {
+  HeadLens r;
+  if (hl) r = *hl; else r.ragged = 0;
+  return r;
+}
+
 // One selection (Section 3.3, Eq. 4 with the stabilizer mask of Section 3.4) for every KV head: scores S[m][cap],
 // units [0, L), n_keep kept per head = the first n_pin units, the best of the middle ones, the last n_stab.
 struct SelectArgs {
@@ -24,12 +39,16 @@ struct SelectArgs {
   int32_t* kept2;       // optional second copy (caller's buffer), or NULL
   int stride2;
   // Optional first step (register-resident form inside the attention launch only): sum the retaining
-  // head's partial scores part[p][m][t], p < n_parts in ascending order, into S_w[m][red_n_c + t] (the rows
+  // head's partial scores part[p][m][t], p < n_parts in ascending order, into S_w[m][L - red_T + t] (the rows
   // of S that the selection then reads) and red_out[m][t]; part == NULL: the scores are already in S.
   const float* part;
-  int n_parts, part_T, h_kv, red_n_c, red_T;
+  int n_parts, part_T, h_kv, red_T;
   float* S_w;
   float* red_out;
+  // Head-wise budgets: L and n_keep per head (ragged == 0: the scalars above); n_stab and n_pin are then the
+  // requested lengths and every head clamps them to its own L: n_stab' = min(n_stab, L), n_pin' = min(n_pin,
+  // L - n_stab').
+  HeadLens L_h, keep_h;
 };
 
 struct Dims {
@@ -66,28 +85,30 @@ void launch_prep_weights(const Dims& D, int expand, const void* W1, const void* 
 // mark_unscored: also store NaN as the score of the appended units (no score will be computed).
 void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c,
                    int64_t seen, const CacheBuf& c, void* qr, const float2* tab, hipStream_t st,
-                   bool mark_unscored = false);
+                   bool mark_unscored = false, const HeadLens* n_c_h = nullptr);
 
 // Attention of T queries (already rotated if rope) over slots [0, n_c+T) of Kx/V, query t seeing
 // slots <= n_c+t (Eq. 1).  Reference-grade VALU kernel, any storage type.
+// n_c_h (every attention launcher): per-head cache lengths, or NULL when all heads hold n_c units.
 void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
-                             int T, int n_c, float scale, hipStream_t st);
+                             int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
 // Software-pipelined bf16 MFMA kernel (d in {64, 96, 128}); false if the shape is not covered.
 bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
-                                int T, int n_c, float scale, hipStream_t st);
+                                int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
 // bf16 MFMA kernel with K/V staged global->LDS directly (d = 128 only); false if the shape is not
 // covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
 bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                               int T, int n_c, float scale, hipStream_t st);
+                               int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
 // The same kernel with the two wavefronts of every SIMD held one S block apart (attention_pp.hip).
 bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx,
                               const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
-                              const SelectArgs* sel = nullptr);
+                              const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr);
 bool attention_pp_fuses_select(const Dims& D, int n_cand);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr,
-                           LaunchTimer tm = LaunchTimer(), const SelectArgs* sel = nullptr);
+                           LaunchTimer tm = LaunchTimer(), const SelectArgs* sel = nullptr,
+                           const HeadLens* n_c_h = nullptr);
 // True when launch_attention_bf16 would carry out a selection over n_cand candidates per head inside its
 // own launch (pass `sel`); otherwise the caller launches launch_select itself.
 bool attention_bf16_fuses_select(const Dims& D, int n_cand);
@@ -97,12 +118,13 @@ bool attention_bf16_rotates_q(const Dims& D);
 // True when launch_attention_bf16 attaches the LaunchTimer's events to the attention kernel's dispatch.
 bool attention_bf16_attaches_timer(const Dims& D);
 
-// Decode step (Eq. 1 with B = 1): one query row per head (rotated if rope) over slots [0, n_keys).
+// Decode step (Eq. 1 with B = 1): one query row per head (rotated if rope) over slots [0, n_keys)
+// (n_keys_h: per KV head, n_keys then being the largest).
 // `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.
 int decode_keys_per_split();
 int decode_max_splits(const Dims& D);
 void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
-                             float scale, float* part, hipStream_t st);
+                             float scale, float* part, hipStream_t st, const HeadLens* n_keys_h = nullptr);
 
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
@@ -115,18 +137,19 @@ void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* 
 // scores[m][t] = sum over nb (fixed order) -> S[m*cap + n_c + t] (if S) and out[m*T + t] (if out).
 // With n_parts == 1 this is a strided copy (used for caller-supplied scores).
 void launch_score_reduce(const float* part, int n_parts, int part_stride_T, int h_kv, int T, float* S,
-                         int cap, int n_c, float* out, hipStream_t st);
-
-
+                         int cap, int n_c, float* out, hipStream_t st, const HeadLens* n_c_h = nullptr);
 
 // Stabilizer-masked top-k per KV head over S[m][0..L): keeps the first n_pin, the last n_stab and the
 // best (n_keep - n_stab - n_pin) of the rest (score desc, index asc); kept[m][0..n_keep) ascending.
 // Requires n_pin + n_stab <= min(L, n_keep).  kept2 (optional, row stride stride2) receives a copy.
 void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int n_pin, int32_t* kept,
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st);
+// The same from a filled SelectArgs (head-wise budgets: L and n_keep are the largest over the heads).
+void launch_select(const SelectArgs& a, int h_kv, hipStream_t st);
 
 // dst[m][r] = src[m][kept[m][r]] for K, V, S, P; dst.Kr[m][r] = K rotated to position r.
+// keep_h: per-head row counts (n_keep then being the largest), or NULL.
 void launch_compact(const Dims& D, const CacheBuf& src, const CacheBuf& dst, const int32_t* kept,
-                    int kept_stride, int n_keep, const float2* tab, hipStream_t st);
+                    int kept_stride, int n_keep, const float2* tab, hipStream_t st, const HeadLens* keep_h = nullptr);
 
 }  // namespace locret

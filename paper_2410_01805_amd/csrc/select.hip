@@ -29,11 +29,7 @@ constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int SEL_HDR = 256 * SEL_REP + 256 + 128;   // words of LDS before the keys: hist[256][32] tot[256] wsum[64] bc[64]
 
 template <bool IN_LDS>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ S, int cap, int L,
-                                                             int n_keep, int n_stab, int n_pin,
-                                                             int32_t* __restrict__ kept,
-                                                             int kept_stride, int32_t* __restrict__ kept2,
-                                                             int stride2) {
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   extern __shared__ uint32_t smem[];
   uint32_t* hist = smem;                       // [256][SEL_REP]
   uint32_t* tot = smem + 256 * SEL_REP;        // [256] per-bin totals
@@ -42,12 +38,17 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
   uint32_t* keys = smem + SEL_HDR;
 
   const int m = blockIdx.x;
-  const float* s = S + (int64_t)m * cap + n_pin;   // candidate c is unit n_pin + c
+  const HeadSel hs = head_sel(a, m);
+  const int L = hs.L, n_pin = hs.n_pin;
+  int32_t* const kept = a.kept;
+  int32_t* const kept2 = a.kept2;
+  const int kept_stride = a.kept_stride, stride2 = a.stride2;
+  const float* s = a.S + (int64_t)m * a.cap + n_pin;   // candidate c is unit n_pin + c
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int n_cand = L - n_stab - n_pin;
-  const int kk = n_keep - n_stab - n_pin;          // candidates to keep, 0 <= kk <= n_cand
+  const int n_cand = L - hs.n_stab - n_pin;
+  const int kk = hs.n_keep - hs.n_stab - n_pin;    // candidates to keep, 0 <= kk <= n_cand
 
   if (IN_LDS)
     for (int i = tid; i < n_cand; i += SEL_THREADS) keys[i] = score_key(s[i]);
@@ -184,10 +185,19 @@ static int lds_limit() {
 
 void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_stab, int n_pin, int32_t* kept,
                    int kept_stride, int32_t* kept2, int stride2, hipStream_t st) {
-  const int n_cand = L - n_stab - n_pin;
+  SelectArgs a = {S, cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2,
+                  nullptr, 0, 0, 0, 0, nullptr, nullptr};
+  a.L_h.ragged = 0;
+  a.keep_h.ragged = 0;
+  launch_select(a, h_kv, st);
+}
+
+// The path is chosen for the longest head; every path takes shorter heads as they come.
+void launch_select(const SelectArgs& a, int h_kv, hipStream_t st) {
+  const int ns = a.n_stab < a.L ? a.n_stab : a.L;
+  const int npin = a.n_pin < a.L - ns ? a.n_pin : a.L - ns;
+  const int n_cand = a.L - ns - npin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
-  const SelectArgs a = {S, cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2,
-                        nullptr, 0, 0, 0, 0, 0, nullptr, nullptr};
   if (wseg <= 12 * 64) {
     hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;
@@ -198,11 +208,9 @@ void launch_select(const float* S, int cap, int h_kv, int L, int n_keep, int n_s
   }
   size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);
   if (need <= (size_t)lds_limit())
-    hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, S, cap, L, n_keep, n_stab,
-                       n_pin, kept, kept_stride, kept2, stride2);
+    hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, a);
   else
-    hipLaunchKernelGGL(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, S,
-                       cap, L, n_keep, n_stab, n_pin, kept, kept_stride, kept2, stride2);
+    hipLaunchKernelGGL(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, a);
 }
 
 }  // namespace locret

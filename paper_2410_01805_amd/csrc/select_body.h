@@ -15,6 +15,18 @@ __device__ __forceinline__ uint32_t score_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// The selection's sizes for KV head m: the common ones, or with head-wise budgets the head's own
+// (the stabilizers and the pinned prefix clamped to what this head holds).
+struct HeadSel { int L, n_keep, n_stab, n_pin; };
+__device__ __forceinline__ HeadSel head_sel(const SelectArgs& a, int m) {
+  HeadSel r;
+  r.L = head_len(a.L_h, m, a.L);
+  r.n_keep = head_len(a.keep_h, m, a.n_keep);
+  r.n_stab = min(a.n_stab, r.L);
+  r.n_pin = min(a.n_pin, r.L - r.n_stab);
+  return r;
+}
+
 constexpr int SEL_REP = 32;    // counter replicas per bin (= LDS banks)
 
 template <int MAXR, int NT>
@@ -25,23 +37,25 @@ __device__ __forceinline__ void select_reg_body(const SelectArgs& a, int m, uint
   uint32_t* tot = hist + 256 * SEL_REP;        // [256]
   uint32_t* wsum = tot + 256;                  // [2][NWAVES]
   uint32_t* bc = wsum + 2 * NWAVES;            // [2]
-  const float* s = a.S + (int64_t)m * a.cap + a.n_pin;   // candidate c is unit n_pin + c
   const int tid = threadIdx.x;
+  const HeadSel hs = head_sel(a, m);
+  const float* s = a.S + (int64_t)m * a.cap + hs.n_pin;   // candidate c is unit n_pin + c
   if (a.part != nullptr) {
+    const int red_n_c = hs.L - a.red_T;
     // the chunk's scores first: the same sum, in the same order, as score_reduce_kernel
     for (int t = tid; t < a.red_T; t += NT) {
       float sum = a.part[(int64_t)m * a.part_T + t];   // a single part is copied bit for bit (-0 stays -0)
       for (int p = 1; p < a.n_parts; ++p) sum += a.part[((int64_t)p * a.h_kv + m) * a.part_T + t];
-      a.S_w[(int64_t)m * a.cap + a.red_n_c + t] = sum;
+      a.S_w[(int64_t)m * a.cap + red_n_c + t] = sum;
       if (a.red_out) a.red_out[(int64_t)m * a.red_T + t] = sum;
     }
     __syncthreads();   // workgroup-scope release/acquire: the keys below are read back from S by other threads
   }
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int L = a.L, n_pin = a.n_pin;
-  const int n_cand = L - a.n_stab - n_pin;
-  const int kk = a.n_keep - a.n_stab - n_pin;
+  const int L = hs.L, n_pin = hs.n_pin;
+  const int n_cand = L - hs.n_stab - n_pin;
+  const int kk = hs.n_keep - hs.n_stab - n_pin;
   const int wseg = ((n_cand + NWAVES - 1) / NWAVES + 63) & ~63;     // <= MAXR * 64 (checked by the host)
   const int w_lo = wave * wseg;
   const int w_hi = min(n_cand, w_lo + wseg);

@@ -15,7 +15,8 @@ namespace locret {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ Kx,
                                                           const T* __restrict__ V, T* __restrict__ out, int Tn,
-                                                          int h, int g, int cap, int n_c, float scale) {
+                                                          int h, int g, int cap, int n_c_common, float scale,
+                                                          HeadLens n_c_h) {
   constexpr int KT = (D > 64) ? 32 : 64;   // keeps K, V, P tiles under 64 KB of LDS
   constexpr int NI = KT / 8;               // keys per thread per tile
   constexpr int DP = D + 4;           // padded row (floats)
@@ -28,6 +29,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const T* __restrict__ 
   const int r = tid >> 3, c = tid & 7;
   const int j = blockIdx.y;
   const int m = j / g;
+  const int n_c = head_len(n_c_h, m, n_c_common);
   const int t0 = blockIdx.x * 32;
   const int t = t0 + r;
   const bool row_ok = t < Tn;
@@ -121,12 +123,12 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(const T* __restrict__ 
 
 template <typename T>
 static void attn_simple_dispatch(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int Tn,
-                                 int n_c, float scale, hipStream_t st) {
+                                 int n_c, float scale, hipStream_t st, const HeadLens& hl) {
   dim3 grid((Tn + 31) / 32, D.h);
 #define LOCRET_ATTN_CASE(DD)                                                                                    \
   case DD:                                                                                                      \
     hipLaunchKernelGGL((attn_simple_kernel<T, DD>), grid, dim3(256), 0, st, (const T*)q, (const T*)Kx,          \
-                       (const T*)V, (T*)out, Tn, D.h, D.g, D.cap, n_c, scale);                                  \
+                       (const T*)V, (T*)out, Tn, D.h, D.g, D.cap, n_c, scale, hl);                              \
     break;
   switch (D.d) {
     LOCRET_ATTN_CASE(16)
@@ -140,9 +142,10 @@ static void attn_simple_dispatch(const Dims& D, const void* q, const void* Kx, c
 }
 
 void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int T,
-                             int n_c, float scale, hipStream_t st) {
-  if (D.bf16) attn_simple_dispatch<bf16_t>(D, q, Kx, V, out, T, n_c, scale, st);
-  else attn_simple_dispatch<float>(D, q, Kx, V, out, T, n_c, scale, st);
+                             int n_c, float scale, hipStream_t st, const HeadLens* n_c_h) {
+  const HeadLens hl = head_lens_or_common(n_c_h);
+  if (D.bf16) attn_simple_dispatch<bf16_t>(D, q, Kx, V, out, T, n_c, scale, st, hl);
+  else attn_simple_dispatch<float>(D, q, Kx, V, out, T, n_c, scale, st, hl);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -228,21 +231,22 @@ void launch_score_simple(const Dims& D, const void* q, const void* k, const void
 
 // ------------------------------------------------------------------------------------------------
 __global__ void score_reduce_kernel(const float* __restrict__ part, int n_parts, int part_T, int h_kv, int Tn,
-                                    float* __restrict__ S, int cap, int n_c, float* __restrict__ out) {
+                                    float* __restrict__ S, int cap, int n_c, float* __restrict__ out,
+                                    HeadLens n_c_h) {
   int gid = blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= h_kv * Tn) return;
   int m = gid / Tn, t = gid % Tn;
   float sum = part[(int64_t)m * part_T + t];   // a single part is copied bit for bit (-0 stays -0)
   for (int p = 1; p < n_parts; ++p) sum += part[((int64_t)p * h_kv + m) * part_T + t];
-  if (S) S[(int64_t)m * cap + n_c + t] = sum;
+  if (S) S[(int64_t)m * cap + head_len(n_c_h, m, n_c) + t] = sum;
   if (out) out[(int64_t)m * Tn + t] = sum;
 }
 
 void launch_score_reduce(const float* part, int n_parts, int part_T, int h_kv, int T, float* S, int cap, int n_c,
-                         float* out, hipStream_t st) {
+                         float* out, hipStream_t st, const HeadLens* n_c_h) {
   int n = h_kv * T;
   hipLaunchKernelGGL(score_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, n_parts, part_T, h_kv, T,
-                     S, cap, n_c, out);
+                     S, cap, n_c, out, head_lens_or_common(n_c_h));
 }
 
 }  // namespace locret

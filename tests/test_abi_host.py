@@ -81,6 +81,8 @@ def test_null_context_is_an_error_everywhere():
     assert B.lib.locret_score(None, 16, 16, 16, 1, 16, None) == B.LOCRET_EINVAL
     assert B.lib.locret_evict_compact(None, 16, 16, 16, 1, 0, None, None) == B.LOCRET_EINVAL
     assert B.lib.locret_cache_len(None) == B.LOCRET_EINVAL
+    assert B.lib.locret_set_head_budgets(None, None) == B.LOCRET_EINVAL
+    assert B.lib.locret_cache_lens(None, None) == B.LOCRET_EINVAL
     assert B.lib.locret_cache_view(None, None, None, None, None, None, None) == B.LOCRET_EINVAL
     B.lib.locret_destroy(None)
 
