@@ -218,6 +218,37 @@ def main():
                             "achieved": round(dec_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / PEAK_HBM_GBS, 4), "timed": "append + split-K attention + merge"}
 
+    # ---- head-wise budgets (next row of the scope table): the same layer with a pyramid of budgets of the
+    # same total, steady state (every head at its budget), against equal budgets measured the same way
+    if w.h_kv >= 2 and w.h_kv <= B.LOCRET_MAX_HEAD_BUDGETS:
+        def steady_ms(lay, n_fill, n_timed=20):
+            qc, kc, vc = chunks[min(1, need - 1)]
+            for _ in range(n_fill):
+                B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
+            s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            s0.record()
+            for _ in range(n_timed):
+                B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
+            s1.record()
+            torch.cuda.synchronize()
+            return s0.elapsed_time(s1) / n_timed
+        B.locret_reset(layer.ctx)                               # the decode steps above left it over its budget
+        equal_ms = steady_ms(layer, (w.b + w.B - 1) // w.B + 4)
+        lo_b = max(w.n_s, w.b // 4)
+        pyr = [int(round(lo_b + (2 * w.b - 2 * lo_b) * (w.h_kv - 1 - m) / (w.h_kv - 1))) for m in range(w.h_kv)]
+        pyr[-1] += w.h_kv * w.b - sum(pyr)                      # exactly the same total
+        import dataclasses
+        lay2 = B.LocretLayer(B.config_from_workload(dataclasses.replace(w, b=max(pyr))), dev)
+        lay2.set_weights(torch.from_numpy(W1h).to(dev).to(td), torch.from_numpy(W2h).to(dev).to(td))
+        lay2.set_head_budgets(pyr)
+        pyr_ms = steady_ms(lay2, (max(pyr) + w.B - 1) // w.B + 4)
+        assert lay2.cache_lens == pyr
+        lay2.close()
+        extra["head_budgets"] = {"budgets": pyr, "steady_ms_per_step": round(pyr_ms, 4),
+                                 "equal_budgets_steady_ms_per_step": round(equal_ms, 4),
+                                 "tokens_per_s": round(w.B / (pyr_ms * 1e-3), 1)}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, host_chunks, args.cpu_rows)

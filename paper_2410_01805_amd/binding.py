@@ -27,6 +27,7 @@ EXPORTS = [
     "locret_set_head_budgets", "locret_cache_lens",
 ]
 LOCRET_PROF_STAGES = 5
+LOCRET_MAX_HEAD_BUDGETS = 64
 PROF_STAGE_NAMES = ("append", "attention", "retaining_head", "select", "compact")
 
 

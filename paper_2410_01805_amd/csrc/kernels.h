@@ -29,6 +29,24 @@ inline HeadLens head_lens_or_common(const HeadLens* hl) {
   return r;
 }
 
+// KV heads from the longest cache to the shortest (ties: lower head first), for launches that hand out
+// the long heads' work first.
+struct HeadOrder {
+  unsigned char v[MAX_HEAD_BUDGETS];
+};
+inline HeadOrder longest_first(const HeadLens& hl, int h_kv) {
+  HeadOrder o;
+  for (int m = 0; m < MAX_HEAD_BUDGETS; ++m) o.v[m] = (unsigned char)m;
+  if (!hl.ragged) return o;
+  for (int i = 1; i < h_kv; ++i) {             // insertion sort: stable, h_kv <= 64
+    const unsigned char x = o.v[i];
+    int j = i;
+    for (; j > 0 && hl.v[o.v[j - 1]] < hl.v[x]; --j) o.v[j] = o.v[j - 1];
+    o.v[j] = x;
+  }
+  return o;
+}
+
 // One selection (Section 3.3, Eq. 4 with the stabilizer mask of Section 3.4) for every KV head: scores S[m][cap],
 // units [0, L), n_keep kept per head = the first n_pin units, the best of the middle ones, the last n_stab.
 struct SelectArgs {

@@ -19,6 +19,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _oracle(w, W1, W2, budgets, n_pin=0):
+    budgets = w.b if budgets is None else budgets         # None: the config's single budget
     return LocretLayerOracle(w.h, w.h_kv, w.d, budgets, W1, W2, w.rh_kv_expand, w.rope, w.theta, n_pin=n_pin)
 
 
@@ -162,6 +163,53 @@ def test_other_launch_orders_with_head_budgets(env, monkeypatch):
     w = synth.tiny(**STREAMS[2][0])
     layer, o = _run_stream(w, STREAMS[2][1])
     torch.cuda.synchronize()
+    _assert_caches_equal(layer, o, w)
+    layer.close()
+
+
+# The head_dim-128 kernel deals its workgroups differently when the heads differ in length and the chunk has a
+# multiple of 8 token tiles: every XCD takes every eighth tile of every head, longest head first, instead of
+# one head per XCD.  LOCRET_PP_SPREAD (read per launch) = 0 keeps one head per XCD, 1 forces the other order.
+SPREAD = dict(name="hb_spread", dtype="bf16", h=16, h_kv=4, d=128, N=3584, B=512, b=1100, n_s=64, d_R=128)
+
+
+@pytest.mark.parametrize("spread,budgets", [(None, [300, 1100, 64, 700]), ("0", [300, 1100, 64, 700]), ("1", None)])
+def test_workgroup_orders_of_the_head_dim_128_kernel(spread, budgets, monkeypatch):
+    if spread is not None:
+        monkeypatch.setenv("LOCRET_PP_SPREAD", spread)
+    w = synth.tiny(**SPREAD)
+    layer, o = _run_stream(w, budgets)
+    _assert_caches_equal(layer, o, w)
+    layer.close()
+
+
+def test_full_size_launch_with_head_budgets():
+    """The Llama-3-8B layer shape of the benchmark configuration (32 query / 8 KV heads x 128, chunks of 4096,
+    2048 stabilizers) with a pyramid of budgets of the same total as 8 x 16384: kept indices bit-exact on every
+    chunk (seeded scores drive the selection on both sides), attention on sampled rows of sampled chunks."""
+    from tests.test_gpu_fullsize import _POOL, _sample_rows
+    import dataclasses
+    budgets = [28672, 25161, 21650, 18139, 14628, 11117, 7606, 4099]
+    w = dataclasses.replace(synth.WORKLOADS["cfg3_llama_128k"], name="cfg3_shape_pyramid", b=max(budgets),
+                            N=11 * 4096, planted_frac=0.0)
+    layer, W1, W2 = make_layer(w)
+    layer.set_head_budgets(budgets)
+    o = _oracle(w, W1, W2, budgets)
+    rng = np.random.default_rng(w.seed)
+    chunks = list(_POOL.map(lambda c: synth.chunk(w, c), range(w.n_chunks)))
+    for c, (q, k, v) in enumerate(chunks):
+        T = q.shape[0]
+        s_in = synth.standard_normal(w.seed, 98, c * w.h_kv * T, w.h_kv * T).reshape(w.h_kv, T).astype(np.float32)
+        rows = _sample_rows(T, rng) if c in (0, 1, 7, 10) else None
+        out_ref = o.attention(q, k, v, rows=rows) if rows is not None else None
+        kept_ref = o.evict_compact(s_in, k, v, w.n_s)
+        out, sc, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), w.n_s,
+                                            scores_in=torch.from_numpy(s_in).to(DEV))
+        _assert_kept_equal(kept, kept_ref, f"chunk {c}")
+        if rows is not None:
+            assert_close(host(out[rows]), out_ref[rows], w.dtype, f"chunk {c} attention", per_row=True)
+            assert_close(sc.cpu().numpy(), o.score(q, k, v), w.dtype, f"chunk {c} scores")
+    assert layer.cache_lens == budgets
     _assert_caches_equal(layer, o, w)
     layer.close()
 
