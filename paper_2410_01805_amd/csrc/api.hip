@@ -20,7 +20,8 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
   size_t K[2], V[2], Kr[2], S[2], P[2];
-  size_t qr, tab, W1t, W2f, part, kept, dpart, total;
+  size_t qr, tab, W1t, W2f, part, kept, dpart, apart, total;
+  size_t apart_floats;
 };
 
 bool valid_head_dim(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
@@ -77,6 +78,8 @@ void make_layout(const locret_config* c, const Dims& D, Layout* L) {
   L->part = take((size_t)max_score_parts(D) * D.h_kv * c->chunk_max * sizeof(float));
   L->kept = take((size_t)D.h_kv * c->budget * sizeof(int32_t));
   L->dpart = take((size_t)D.h * decode_max_splits(D) * (D.d + 2) * sizeof(float));
+  L->apart_floats = attention_pp_split_floats(D, c->chunk_max);
+  L->apart = take(L->apart_floats * sizeof(float));
   L->total = off;
 }
 
@@ -336,6 +339,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const void* Kx = D.rope ? A.Kr : A.K;
   const int n_c = c->n_c;
   const int L = n_c + T;
+  float* split_part = c->L.apart_floats ? (float*)(c->ws + c->L.apart) : nullptr;
   auto attention = [&](const SelectArgs* sel) {
     // when profiling, the matrix-core kernels are timed through their own dispatch
     const bool prof = c->prof_calls < c->prof_max;
@@ -343,11 +347,13 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
       LaunchTimer tm;
       tm.start = c->prof_event(1, 0);
       tm.stop = c->prof_event(1, 1);
-      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel, hl);
+      launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel, hl,
+                            split_part, c->L.apart_floats);
       return;
     }
     c->mark(1, 0, st);
-    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, LaunchTimer(), sel, hl);
+    if (c->mfma_attn) launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, LaunchTimer(), sel, hl,
+                                            split_part, c->L.apart_floats);
     else launch_attention_simple(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, hl);
     c->mark(1, 1, st);
   };

@@ -441,10 +441,10 @@ bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel,
-                           const HeadLens* n_c_h) {
+                           const HeadLens* n_c_h, float* split_part, size_t split_floats) {
   const int v = attn_variant();
   const HeadLens hl = head_lens_or_common(n_c_h);
-  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h)) return;
+  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h, split_part, split_floats)) return;
   if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
   if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
 #define LOCRET_CASE(DD)                                                                           \

@@ -53,16 +53,24 @@ constexpr int PP_KPRE = 4;                     // K fragments fetched ahead of t
 constexpr int PP_VPRE = 4;                     // V^T fragments in flight ahead of their MFMA
 constexpr int PP_YTAIL = 4;                    // MFMAs of group A's S block issued behind barrier Y
 constexpr int PP_SEL_MAXR = 48;                // keys per thread of a selection workgroup (512 threads)
+constexpr int PP_MAX_SPLIT = 8;                // key ranges per (head group, token tile) item at most
+constexpr int PP_SPLIT_TOKENS = 2048;          // token rows (times splits) the partial-result buffer holds at most
 
 #define LOCRET_TR_READ(dst, addr, off) \
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
 #define LOCRET_LGKM_WAIT(a, b, n) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "i"(n))
 
+// SPLIT = false: the whole key range per workgroup (n_split_arg and part_arg are ignored, so nothing of the
+// key split remains in the code of the common case).
+template <bool SPLIT>
 __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c_common, float c_log2,
                                                              int hpw, int n_hgroups, int n_ttiles, SelectArgs sel, int n_sel,
-                                                             HeadLens n_c_h, int spread, HeadOrder order) {
+                                                             HeadLens n_c_h, int spread, HeadOrder order,
+                                                             int n_split_arg, float* __restrict__ part_arg) {
+  const int n_split = SPLIT ? n_split_arg : 1;
+  float* const part = SPLIT ? part_arg : nullptr;
   constexpr int NW = PP_NW;
   constexpr int D = PP_D;
   constexpr int NKS = D / 16;
@@ -104,7 +112,9 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
     hgroup = bid % n_hgroups;
     tt = bid / n_hgroups;
   }
-  tt = n_ttiles - 1 - tt;                      // longest key ranges first
+  // n_split > 1: n_ttiles counts (token tile, key split) pairs, the split being the fast index
+  const int split = tt % n_split;
+  tt = n_ttiles / n_split - 1 - tt / n_split;  // longest key ranges first
   const int wph = NW / hpw;
   const int TW = wph * 32;
   const int t0 = tt * TW;
@@ -114,7 +124,13 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   const int tw0 = t0 + (wave % wph) * 32;
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;
-  const int n_tiles = (n_keys + KT - 1) / KT;
+  const int n_tiles_all = (n_keys + KT - 1) / KT;
+  // Key split (short chunks leave most CUs without a workgroup otherwise): this workgroup takes the key tiles
+  // [t_lo, t_lo + n_tiles) of its queries' range and leaves un-normalised partial results for the merge kernel.
+  const int per_split = (n_tiles_all + n_split - 1) / n_split;
+  const int t_lo = split * per_split;
+  const int n_tiles = max(0, min(n_tiles_all, t_lo + per_split) - t_lo);
+  const int n_keys_s = min(n_keys, (t_lo + n_tiles) * KT);
   const int wave_last_slot = n_c + min(Tn - 1, tw0 + 31);
   const int my_t = min(tw0 + n32, Tn - 1);
   const int limit = n_c + my_t;
@@ -188,7 +204,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   const int v_vo = w4 * 1024 + l_row * 256 + ((l_pos ^ (l_row << 2)) * 16);
   auto issue = [&](int tile, int stage) __attribute__((always_inline)) {
     const int tile_u = __builtin_amdgcn_readfirstlane(tile);
-    const int left = __builtin_amdgcn_readfirstlane(max(n_keys - tile_u * KT, 0) * (D * 2));   // 0 past the end
+    const int left = __builtin_amdgcn_readfirstlane(max(n_keys_s - tile_u * KT, 0) * (D * 2));   // 0 past the end
     __amdgpu_buffer_rsrc_t kr =
         __builtin_amdgcn_make_buffer_rsrc((void*)(Kb + (int64_t)tile_u * (KT * D)), 0, left, 0x00020000);
     __amdgpu_buffer_rsrc_t vr =
@@ -356,27 +372,27 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   };
 
   // tiles this wavefront's queries can see (wave-uniform, <= n_tiles): later tiles only keep the barriers
-  const int n_active = min(n_tiles, wave_last_slot / KT + 1);
+  const int n_active = max(0, min(n_tiles, wave_last_slot / KT + 1 - t_lo));
   if (isB) {
-    issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
+    issue(t_lo, 0);
+    issue(t_lo + 1, 1);
+    issue(t_lo + 2, 2);
     asm volatile("s_waitcnt vmcnt(8)" ::: "memory");            // tiles 0 and 1 have landed
     wg_barrier();
     for (int t = 0; t < n_active; ++t) {
       const int sb_off = (t & 3) * PP_STAGE_B;
       wg_barrier();                                              // X(t)
-      issue(t + 3, (t + 3) & 3);
+      issue(t_lo + t + 3, (t + 3) & 3);
       prefetch_k(sb_off);
       wg_barrier();                                              // Y(t)
       f32x16 sacc[2];
       s_block(sacc, sb_off, []() {}, IntC<0>());
-      softmax_pv(sacc, t, sb_off);
+      softmax_pv(sacc, t_lo + t, sb_off);
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");          // own loads of tile t+2 have landed
     }
     for (int t = n_active; t < n_tiles; ++t) {
       wg_barrier();
-      issue(t + 3, (t + 3) & 3);
+      issue(t_lo + t + 3, (t + 3) & 3);
       wg_barrier();
       asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     }
@@ -388,7 +404,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
       wg_barrier();                                              // X(t)
       f32x16 sacc[2];
       s_block(sacc, sb_off, wg_barrier, IntC<PP_YTAIL>());        // Y(t), passed PP_YTAIL MFMAs before the end of the block
-      softmax_pv(sacc, t, sb_off);
+      softmax_pv(sacc, t_lo + t, sb_off);
       prefetch_k(((t + 1) & 3) * PP_STAGE_B);
     }
     for (int t = n_active; t < n_tiles; ++t) {
@@ -402,7 +418,24 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   {
     const int t = tw0 + n32;
     float l = l_run + __shfl_xor(l_run, 32, 64);
-    if (t < Tn) {
+    if (part != nullptr) {
+      // partial result of this key split: O un-normalised, running max (log2 units) and sum; a wavefront that saw
+      // no key leaves sum 0
+      if (t < Tn) {
+        const int64_t row = ((int64_t)split * Tn + t) * h + j;
+        float* op = part + row * D;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq)
+            *(float4*)(op + db * 32 + rq * 8 + hi * 4) =
+                make_float4(oacc[db][rq * 4 + 0], oacc[db][rq * 4 + 1], oacc[db][rq * 4 + 2], oacc[db][rq * 4 + 3]);
+        if (hi == 0) {
+          float* ml = part + (int64_t)n_split * Tn * h * D + row * 2;
+          *(float2*)ml = make_float2(m_run, l);
+        }
+      }
+    } else if (t < Tn) {
       const float inv = 1.f / l;
       bf16_t* op = out + ((int64_t)t * h + j) * D;
 #pragma unroll
@@ -418,6 +451,47 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   }
 }
 
+// out[t][j][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m) over the key splits of a row (t, j);
+// a split whose sum is 0 saw no key of that row.  A thread owns 4 elements of a row.
+__global__ __launch_bounds__(256) void attn_pp_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
+                                                            int rows, int n_split) {
+  constexpr int D = PP_D;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = gid / (D / 4);
+  const int e = (int)(gid % (D / 4)) * 4;
+  if (row >= rows) return;
+  const float* ml = part + (int64_t)n_split * rows * D;
+  float M = -INFINITY;
+  for (int s = 0; s < n_split; ++s) {
+    const float2 x = *(const float2*)(ml + ((int64_t)s * rows + row) * 2);
+    if (x.y > 0.f) M = fmaxf(M, x.x);
+  }
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, den = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    const float2 x = *(const float2*)(ml + ((int64_t)s * rows + row) * 2);
+    if (!(x.y > 0.f)) continue;
+    const float w = __builtin_amdgcn_exp2f(x.x - M);
+    const float4 o = *(const float4*)(part + ((int64_t)s * rows + row) * D + e);
+    den = fmaf(w, x.y, den);
+    a0 = fmaf(w, o.x, a0);
+    a1 = fmaf(w, o.y, a1);
+    a2 = fmaf(w, o.z, a2);
+    a3 = fmaf(w, o.w, a3);
+  }
+  const float inv = 1.f / den;      // every query sees at least its own key
+  uint2 wd;
+  wd.x = pack_bf16(a0 * inv, a1 * inv);
+  wd.y = pack_bf16(a2 * inv, a3 * inv);
+  *(uint2*)(out + row * D + e) = wd;
+}
+
+// Floats of workspace for the partial results of key-split launches (0: this shape never splits).
+size_t attention_pp_split_floats(const Dims& Dm, int chunk_max) {
+  if (Dm.d != PP_D || !Dm.bf16) return 0;
+  const int tokens = chunk_max < PP_SPLIT_TOKENS / 2 ? 2 * chunk_max : PP_SPLIT_TOKENS;
+  return (size_t)tokens * Dm.h * (PP_D + 2);
+}
+
 // `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
 bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
   if (Dm.d != PP_D || (int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;
@@ -428,7 +502,7 @@ bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
 // `sel` non-null (and attention_pp_fuses_select true): the launch also performs that selection.
 bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                               int T, int n_c, float scale, hipStream_t st, const SelectArgs* sel,
-                              const HeadLens* n_c_h) {
+                              const HeadLens* n_c_h, float* split_part, size_t split_floats) {
   if (Dm.d != PP_D) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
   constexpr int NW = PP_NW;
@@ -442,11 +516,41 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
   const int n_sel = sel ? Dm.h_kv : 0;
   const char* sp_e = getenv("LOCRET_PP_SPREAD");
   const HeadLens hl = head_lens_or_common(n_c_h);
-  const int spread = n_ttiles % 8 == 0 && ((hl.ragged && !(sp_e && sp_e[0] == '0')) || (sp_e && sp_e[0] == '1'));
   const SelectArgs sa = sel ? *sel : SelectArgs{};
-  hipExtLaunchKernelGGL(attn_pp_kernel, dim3(n_sel + n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop, 0,
-                        (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c,
-                        c_log2, hpw, n_hgroups, n_ttiles, sa, n_sel, hl, spread, longest_first(hl, Dm.h_kv));
+  // Key split: a short chunk has too few (head group, token tile) items for the 256 CUs (chunks of 1024 tokens of
+  // a 32-head layer: 128), so each item is cut into n_split key ranges, as many as bring the launch to about one
+  // workgroup per CU, and a second kernel merges the partial results.  Only while every split still has a
+  // few key tiles in every head and the partials fit their buffer.  LOCRET_PP_SPLIT (read per launch): 0 = never,
+  // k = always k ranges (bounded by the buffer only).
+  int n_split = 1;
+  if (split_part != nullptr) {
+    const char* se = getenv("LOCRET_PP_SPLIT");
+    const int forced = se ? atoi(se) : -1;
+    int min_nc = n_c;
+    if (hl.ragged) for (int m = 0; m < Dm.h_kv; ++m) min_nc = hl.v[m] < min_nc ? hl.v[m] : min_nc;
+    const int items = n_hgroups * n_ttiles;
+    int want = forced >= 0 ? forced : 256 / items;
+    want = want > PP_MAX_SPLIT ? PP_MAX_SPLIT : want;
+    const int min_tiles = (min_nc + 1 + KT - 1) / KT;
+    while (want > 1 && ((size_t)want * T * Dm.h * (PP_D + 2) > split_floats || (forced < 0 && min_tiles / want < 8))) --want;
+    n_split = want < 1 ? 1 : want;
+  }
+  const int n_tt_eff = n_ttiles * n_split;
+  const int spread = n_tt_eff % 8 == 0 && ((hl.ragged && !(sp_e && sp_e[0] == '0')) || (sp_e && sp_e[0] == '1'));
+  float* part = n_split > 1 ? split_part : nullptr;
+#define LOCRET_PP_LAUNCH(SP)                                                                                          \
+  hipExtLaunchKernelGGL(attn_pp_kernel<SP>, dim3(n_sel + n_hgroups * n_tt_eff), dim3(NW * 64), 0, st, tm.start,         \
+                        part ? nullptr : tm.stop, 0, (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V,        \
+                        (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw, n_hgroups, n_tt_eff, sa, n_sel, hl, spread, \
+                        longest_first(hl, Dm.h_kv), n_split, part)
+  if (part) LOCRET_PP_LAUNCH(true); else LOCRET_PP_LAUNCH(false);
+#undef LOCRET_PP_LAUNCH
+  if (part) {
+    const int rows = T * Dm.h;
+    const int64_t threads = (int64_t)rows * (PP_D / 4);
+    hipExtLaunchKernelGGL(attn_pp_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, nullptr, tm.stop, 0,
+                          (const float*)part, (bf16_t*)out, rows, n_split);
+  }
   return true;
 }
 

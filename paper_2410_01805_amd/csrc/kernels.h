@@ -120,13 +120,17 @@ bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const
 // The same kernel with the two wavefronts of every SIMD held one S block apart (attention_pp.hip).
 bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx,
                               const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
-                              const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr);
+                              const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr,
+                              float* split_part = nullptr, size_t split_floats = 0);
+// Floats of scratch the head_dim-128 kernel wants for launches that split the key range (short chunks);
+// 0 when the shape never splits.  Without the buffer it does not split.
+size_t attention_pp_split_floats(const Dims& D, int chunk_max);
 bool attention_pp_fuses_select(const Dims& D, int n_cand);
 // bf16 MFMA kernel (d in {64, 96, 128}).
 void launch_attention_bf16(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                            int T, int n_c, float scale, hipStream_t st, const float2* q_rot_tab = nullptr,
                            LaunchTimer tm = LaunchTimer(), const SelectArgs* sel = nullptr,
-                           const HeadLens* n_c_h = nullptr);
+                           const HeadLens* n_c_h = nullptr, float* split_part = nullptr, size_t split_floats = 0);
 // True when launch_attention_bf16 would carry out a selection over n_cand candidates per head inside its
 // own launch (pass `sel`); otherwise the caller launches launch_select itself.
 bool attention_bf16_fuses_select(const Dims& D, int n_cand);

@@ -78,6 +78,12 @@ WORKLOADS: dict[str, Workload] = {
                                True, 10000.0, _SEED0 + 4),
     "cfg5_stream_1m": Workload("cfg5_stream_1m", "bf16", 32, 8, 128, 1048576, 4096, 8192, 2048, 1024, 0,
                                True, 500000.0, _SEED0 + 5),
+    # the paper's own inference settings (Appendix "Hyperparameters, Environment and Baselines", inference
+    # table: budget b, chunk B, stabilizers n_s) on the two backbones' layer shapes, 128K tokens
+    "paper_llama31_row": Workload("paper_llama31_row", "bf16", 32, 8, 128, 131072, 1024, 16384, 2500, 1024, 0,
+                                  True, 500000.0, _SEED0 + 6),
+    "paper_phi3_row": Workload("paper_phi3_row", "bf16", 32, 32, 96, 131072, 3072, 6000, 2500, 1024, 0,
+                               True, 10000.0, _SEED0 + 7),
 }
 
 

@@ -183,6 +183,14 @@ def test_workgroup_orders_of_the_head_dim_128_kernel(spread, budgets, monkeypatc
     layer.close()
 
 
+def test_key_split_with_head_budgets(monkeypatch):
+    monkeypatch.setenv("LOCRET_PP_SPLIT", "4")         # 8 token tiles x 4 key ranges, dealt over the XCDs longest head first
+    w = synth.tiny(**SPREAD)
+    layer, o = _run_stream(w, [300, 1100, 64, 700])
+    _assert_caches_equal(layer, o, w)
+    layer.close()
+
+
 def test_full_size_launch_with_head_budgets():
     """The Llama-3-8B layer shape of the benchmark configuration (32 query / 8 KV heads x 128, chunks of 4096,
     2048 stabilizers) with a pyramid of budgets of the same total as 8 x 16384: kept indices bit-exact on every

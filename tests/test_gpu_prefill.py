@@ -130,6 +130,31 @@ def test_alternative_attention_kernels(kw, variant, monkeypatch):
     layer.close()
 
 
+@pytest.mark.parametrize("n_split", ["2", "3", "8"])
+def test_key_split_of_the_head_dim_128_kernel_forced(n_split, monkeypatch):
+    # LOCRET_PP_SPLIT=k (read per launch) cuts every (head group, token tile) item into k key ranges whose partial
+    # results a second kernel merges, whatever the sizes: the first chunks, with fewer key tiles than ranges,
+    # leave ranges empty, and in the range that holds the diagonal some wavefronts see no key
+    monkeypatch.setenv("LOCRET_PP_SPLIT", n_split)
+    for kw in (SMALL[4], SMALL[7]):
+        w = synth.tiny(**kw)
+        layer, o, _ = _run_stream(w, teacher_forced=True)
+        layer.close()
+
+
+def test_key_split_chosen_for_short_chunks_behind_a_long_cache():
+    # 4 items per launch at 128-token chunks: the launcher splits the keys 8 ways once the cache is long enough
+    # (every range at least 8 key tiles), and not before; the tail pass of Algorithm 1 (evict = 0) as well
+    w = synth.tiny(name="short_chunks", dtype="bf16", h=8, h_kv=2, d=128, N=6 * 1024 + 5 * 128 + 100, B=1024, b=4600,
+                   n_s=100, d_R=128)
+    sizes = [1024] * 6 + [128] * 5 + [100]
+    layer, o, _ = _run_stream(w, teacher_forced=True, chunk_sizes=sizes, last_chunk_unmasked=True)
+    K, V, S, P = layer.cache_tensors()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+    layer.close()
+
+
 def test_selection_as_its_own_launch(monkeypatch):
     # by default the head_dim-128 attention launch carries the selection in its first workgroups;
     # LOCRET_FUSE_SELECT=0 (read per call) launches it separately: same kept indices either way
