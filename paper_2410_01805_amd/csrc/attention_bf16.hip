@@ -42,7 +42,8 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
                                                              const bf16_t* __restrict__ Kx, const bf16_t* __restrict__ V,
                                                              bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c_common, float c_log2,
-                                                             int hpw, int n_hgroups, int n_ttiles, HeadLens n_c_h) {
+                                                             int hpw, int n_hgroups, int n_ttiles, HeadLens n_c_h,
+                                                             int spread, HeadOrder order) {
   constexpr int NKS = D / 16;          // k-steps over the head dim for S
   constexpr int NDB = D / 32;          // 32-row blocks of O^T
   constexpr int KCH = D / 8;           // 16-byte chunks per K row
@@ -62,7 +63,16 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
   // ---- head group is taken from id % 8 to keep one KV head's K/V in one XCD's L2 --------------
   const int bid = blockIdx.x;
   int hgroup, tt;
-  if ((n_hgroups & 7) == 0) {
+  if (spread) {
+    // KV heads of different cache lengths (head-wise budgets): every XCD takes every eighth token tile of
+    // every head, longest head first, so that no XCD is left with the long heads (see attention_pp.hip)
+    const int i = bid >> 3, per_head = (n_ttiles + 7) >> 3;
+    const int r = i / per_head;
+    const int gph = g / hpw;                               // head groups per KV head
+    hgroup = order.v[r / gph] * gph + r % gph;
+    tt = (i % per_head) * 8 + (bid & 7);
+    if (tt >= n_ttiles) return;                            // the launch is padded to whole rounds of the 8 XCDs
+  } else if ((n_hgroups & 7) == 0) {
     const int g8 = n_hgroups >> 3;
     hgroup = (bid & 7) * g8 + (bid >> 3) % g8;
     tt = bid / n_hgroups;
@@ -399,10 +409,13 @@ static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const flo
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  hipExtLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_hgroups * n_ttiles), dim3(NW * 64), 0, st, tm.start, tm.stop,
+  const char* sp_e = getenv("LOCRET_PP_SPREAD");
+  const int spread = hl.ragged && !(sp_e && sp_e[0] == '0');
+  const int n_wg = spread ? n_hgroups * ((n_ttiles + 7) / 8) * 8 : n_hgroups * n_ttiles;
+  hipExtLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_wg), dim3(NW * 64), 0, st, tm.start, tm.stop,
                         0, (const bf16_t*)q, tab,
                      (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw,
-                     n_hgroups, n_ttiles, hl);
+                     n_hgroups, n_ttiles, hl, spread, longest_first(hl, Dm.h_kv));
 }
 
 // LOCRET_ATTN_VARIANT selects a kernel for experiments: default "pp" (direct-to-LDS staging with the two

@@ -99,11 +99,12 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
     // the shortest, so that all XCDs hold the same work and each hands out its long items first.
     // (Measured on 8 heads of 28672 ... 4096 units, mean 16384: 1.61 ms per step with one head per XCD,
     // 1.39 ms with the heads interleaved item by item, 1.14 ms in this order; equal heads 1.07 ms.)
-    const int i = bid >> 3, per_head = n_ttiles >> 3;      // n_ttiles % 8 == 0 (host)
+    const int i = bid >> 3, per_head = (n_ttiles + 7) >> 3;
     const int r = i / per_head;                            // rank of the head group, longest first
     const int gph = g / hpw;                               // head groups per KV head
     hgroup = order.v[r / gph] * gph + r % gph;
     tt = (i % per_head) * 8 + (bid & 7);
+    if (tt >= n_ttiles) return;                            // the launch is padded to whole rounds of the 8 XCDs
   } else if ((n_hgroups & 7) == 0) {                  // one KV head per XCD (workgroup ids go round the XCDs)
     const int g8 = n_hgroups >> 3;
     hgroup = (blockIdx.x & 7) * g8 + (bid >> 3) % g8;
@@ -536,10 +537,11 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
     n_split = want < 1 ? 1 : want;
   }
   const int n_tt_eff = n_ttiles * n_split;
-  const int spread = n_tt_eff % 8 == 0 && ((hl.ragged && !(sp_e && sp_e[0] == '0')) || (sp_e && sp_e[0] == '1'));
+  const int spread = (hl.ragged && !(sp_e && sp_e[0] == '0')) || (sp_e && sp_e[0] == '1');
+  const int n_wg = spread ? n_hgroups * ((n_tt_eff + 7) / 8) * 8 : n_hgroups * n_tt_eff;
   float* part = n_split > 1 ? split_part : nullptr;
 #define LOCRET_PP_LAUNCH(SP)                                                                                          \
-  hipExtLaunchKernelGGL(attn_pp_kernel<SP>, dim3(n_sel + n_hgroups * n_tt_eff), dim3(NW * 64), 0, st, tm.start,         \
+  hipExtLaunchKernelGGL(attn_pp_kernel<SP>, dim3(n_sel + n_wg), dim3(NW * 64), 0, st, tm.start,                         \
                         part ? nullptr : tm.stop, 0, (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V,        \
                         (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw, n_hgroups, n_tt_eff, sa, n_sel, hl, spread, \
                         longest_first(hl, Dm.h_kv), n_split, part)

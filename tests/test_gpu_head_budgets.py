@@ -167,9 +167,9 @@ def test_other_launch_orders_with_head_budgets(env, monkeypatch):
     layer.close()
 
 
-# The head_dim-128 kernel deals its workgroups differently when the heads differ in length and the chunk has a
-# multiple of 8 token tiles: every XCD takes every eighth tile of every head, longest head first, instead of
-# one head per XCD.  LOCRET_PP_SPREAD (read per launch) = 0 keeps one head per XCD, 1 forces the other order.
+# The matrix-core attention kernels deal their workgroups differently when the heads differ in length: every XCD
+# takes every eighth token tile of every head, longest head first, instead of one head per XCD (8 token tiles here:
+# whole rounds of the 8 XCDs; the other streams of this file have tile counts that leave the last round short).  LOCRET_PP_SPREAD (read per launch) = 0 keeps one head per XCD, 1 forces the other order.
 SPREAD = dict(name="hb_spread", dtype="bf16", h=16, h_kv=4, d=128, N=3584, B=512, b=1100, n_s=64, d_R=128)
 
 
@@ -179,6 +179,14 @@ def test_workgroup_orders_of_the_head_dim_128_kernel(spread, budgets, monkeypatc
         monkeypatch.setenv("LOCRET_PP_SPREAD", spread)
     w = synth.tiny(**SPREAD)
     layer, o = _run_stream(w, budgets)
+    _assert_caches_equal(layer, o, w)
+    layer.close()
+
+
+def test_workgroup_order_of_the_other_head_dims_with_head_budgets():
+    # head_dim 96 (register-staged kernel, 256 tokens per workgroup): 8 token tiles
+    w = synth.tiny(name="hb_spread_d96", dtype="bf16", h=4, h_kv=4, d=96, N=3 * 2048, B=2048, b=2500, n_s=64, d_R=128)
+    layer, o = _run_stream(w, [2500, 300, 1200, 64])
     _assert_caches_equal(layer, o, w)
     layer.close()
 
