@@ -21,13 +21,23 @@ FLAGS = [
 ]
 
 
+# Per-file additions.  attention_pp.hip: every basic block that is not fallen into starts on a 256-byte
+# boundary.  The two tile loops of that kernel are long straight runs of instructions; where they happened to
+# start relative to the instruction-fetch lines moved the step time of the benchmark configuration by 0.6 %
+# between builds whose loops were instruction for instruction the same (measured, same box), so the placement
+# is fixed instead of left to what precedes the loops.
+FILE_FLAGS = {
+    "attention_pp.hip": ["-mllvm", "-align-all-nofallthru-blocks=8"],
+}
+
+
 def sources() -> list[str]:
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def _compile(src: str, extra: list[str]) -> str:
     obj = os.path.join(OBJDIR, os.path.basename(src)[:-4] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *FILE_FLAGS.get(os.path.basename(src), []), *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")

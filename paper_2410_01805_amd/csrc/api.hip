@@ -22,6 +22,7 @@ struct Layout {
   size_t K[2], V[2], Kr[2], S[2], P[2];
   size_t qr, tab, W1t, W2f, part, kept, dpart, apart, total;
   size_t apart_floats;
+  size_t zpart, zpart_floats;
 };
 
 bool valid_head_dim(int d) { return d == 16 || d == 32 || d == 64 || d == 96 || d == 128; }
@@ -80,6 +81,8 @@ void make_layout(const locret_config* c, const Dims& D, Layout* L) {
   L->dpart = take((size_t)D.h * decode_max_splits(D) * (D.d + 2) * sizeof(float));
   L->apart_floats = attention_pp_split_floats(D, c->chunk_max);
   L->apart = take(L->apart_floats * sizeof(float));
+  L->zpart_floats = score_bf16_split_floats(D, c->chunk_max);
+  L->zpart = take(L->zpart_floats * sizeof(float));
   L->total = off;
 }
 
@@ -243,8 +246,8 @@ static void run_score(locret_ctx* c, const void* q, const void* k, const void* v
   float* part = (float*)(c->ws + c->L.part);
   int parts;
   if (c->mfma_score) {
-    launch_score_bf16(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
-    parts = score_parts_bf16(c->D);
+    parts = launch_score_bf16(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st,
+                              c->L.zpart_floats ? (float*)(c->ws + c->L.zpart) : nullptr, c->L.zpart_floats);
   } else {
     launch_score_simple(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
     parts = score_parts_simple(c->D);

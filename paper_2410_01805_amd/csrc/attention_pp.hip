@@ -60,17 +60,19 @@ constexpr int PP_SPLIT_TOKENS = 2048;          // token rows (times splits) the 
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
 #define LOCRET_LGKM_WAIT(a, b, n) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "i"(n))
 
-// SPLIT = false: the whole key range per workgroup (n_split_arg and part_arg are ignored, so nothing of the
-// key split remains in the code of the common case).
-template <bool SPLIT>
+// GENERAL = false is the common case: every KV head holds n_c_common units, one KV head per XCD, the whole key
+// range per workgroup (n_c_h, spread_arg, order, n_split_arg and part_arg are ignored, so nothing of head-wise
+// lengths, the spread launch order or the key split remains in its code).
+template <bool GENERAL>
 __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c_common, float c_log2,
                                                              int hpw, int n_hgroups, int n_ttiles, SelectArgs sel, int n_sel,
-                                                             HeadLens n_c_h, int spread, HeadOrder order,
+                                                             HeadLens n_c_h, int spread_arg, HeadOrder order,
                                                              int n_split_arg, float* __restrict__ part_arg) {
-  const int n_split = SPLIT ? n_split_arg : 1;
-  float* const part = SPLIT ? part_arg : nullptr;
+  const int n_split = GENERAL ? n_split_arg : 1;
+  float* const part = GENERAL ? part_arg : nullptr;
+  const int spread = GENERAL ? spread_arg : 0;
   constexpr int NW = PP_NW;
   constexpr int D = PP_D;
   constexpr int NKS = D / 16;
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   const int t0 = tt * TW;
   const int j = hgroup * hpw + wave / wph;
   const int m = (hgroup * hpw) / g;
-  const int n_c = __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common));   // this KV head's cache length
+  const int n_c = GENERAL ? __builtin_amdgcn_readfirstlane(head_len(n_c_h, m, n_c_common)) : n_c_common;   // this KV head's cache length
   const int tw0 = t0 + (wave % wph) * 32;
   const int t_last_wg = min(Tn, t0 + TW) - 1;
   const int n_keys = n_c + t_last_wg + 1;
@@ -545,7 +547,7 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
                         part ? nullptr : tm.stop, 0, (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V,        \
                         (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw, n_hgroups, n_tt_eff, sa, n_sel, hl, spread, \
                         longest_first(hl, Dm.h_kv), n_split, part)
-  if (part) LOCRET_PP_LAUNCH(true); else LOCRET_PP_LAUNCH(false);
+  if (part || spread || hl.ragged) LOCRET_PP_LAUNCH(true); else LOCRET_PP_LAUNCH(false);
 #undef LOCRET_PP_LAUNCH
   if (part) {
     const int rows = T * Dm.h;

@@ -154,8 +154,11 @@ int score_parts_simple(const Dims& D);
 int score_parts_bf16(const Dims& D);
 void launch_score_simple(const Dims& D, const void* q, const void* k, const void* v, int T,
                          const void* W1t, const float* W2f, float* part, hipStream_t st);
-void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T,
-                       const void* W1t, const float* W2f, float* part, hipStream_t st);
+// Returns the number of partials it wrote (1 when it split the contraction instead, which needs `zpart`).
+int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T,
+                      const void* W1t, const float* W2f, float* part, hipStream_t st, float* zpart = nullptr,
+                      size_t zpart_floats = 0);
+size_t score_bf16_split_floats(const Dims& D, int chunk_max);
 // scores[m][t] = sum over nb (fixed order) -> S[m*cap + n_c + t] (if S) and out[m*T + t] (if out).
 // With n_parts == 1 this is a strided copy (used for caller-supplied scores).
 void launch_score_reduce(const float* part, int n_parts, int part_stride_T, int h_kv, int T, float* S,

@@ -58,11 +58,16 @@ __device__ __forceinline__ float sum_across_halves(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// KSPLIT (short chunks, too few 128 x 128 tiles for the CUs): blockIdx.z takes a slice of the contraction and
+// the workgroup leaves its partial pre-activations zpart[z][t][r]; score_finish_kernel sums the slices and
+// applies SiLU and W2.  KSPLIT = false: the whole contraction, epilogue below.
+template <bool KSPLIT>
 __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, int Tn, int hd, int kvd,
                                                          const bf16_t* __restrict__ W1t,
                                                          const float* __restrict__ W2f, int K, int h_kv,
-                                                         float* __restrict__ part, int part_T) {
+                                                         float* __restrict__ part, int part_T,
+                                                         float* __restrict__ zpart, int d_R) {
   __shared__ __attribute__((aligned(1024))) ScoreSmem sm;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -91,14 +96,19 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   const int l_csw1 = ((lane & 7) ^ (l_row >> 1) ^ 4) * 16;
   const int a_vo = (pw * 32 + l_row) * (K * 2);        // + ii * 8 rows + chunk offset
   const int b_row = pw * 32 + l_row;                     // + ii * 8
-  const int n_stages = K / RT_K;
+  const int n_stages_all = K / RT_K;
+  // this workgroup's stages: [s_lo, s_lo + n_stages)
+  const int per_z = KSPLIT ? (n_stages_all + (int)gridDim.z - 1) / (int)gridDim.z : n_stages_all;
+  const int s_lo = KSPLIT ? (int)blockIdx.z * per_z : 0;
+  const int n_stages = KSPLIT ? max(0, min(n_stages_all, s_lo + per_z) - s_lo) : n_stages_all;
   const int q_stages = hd / RT_K, k_stages = kvd / RT_K;
   const int rows_left = min(max(Tn - t0, 0), RT_N);    // valid token rows of this workgroup
 
-  auto issue = [&](int s, int buf) {
+  auto issue = [&](int s_rel, int buf) {
     // (a stage past the last one would get empty descriptors: zeros, no memory access; the loops below
     // do not ask for one: 24 such loads per producer at the end kept every wavefront waiting ~4000 cycles)
-    const bool live = s < n_stages;
+    const bool live = s_rel < n_stages;
+    const int s = s_lo + s_rel;
     {
       __amdgpu_buffer_rsrc_t ar = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(W1t + (int64_t)r0 * K + (int64_t)s * RT_K), 0, live ? (RT_M * K * 2 - s * RT_K * 2) : 0, 0x00020000);
@@ -184,7 +194,9 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   // most one stage = 8 of its loads is still in flight) and every consumer has left stage s-1.  Behind it a
   // producer starts stage s+3 in the buffer of stage s-1; a consumer computes stage s and then requests the
   // first fragments of stage s+1.  A bare s_barrier: __syncthreads() would first drain every load in flight.
-  if (producer) {
+  if (n_stages == 0) {
+    // an empty slice (the host does not launch one): both roles skip the pipeline, the partial is zero
+  } else if (producer) {
     issue(0, 0);
     if (1 < n_stages) issue(1, 1);
     if (2 < n_stages) issue(2, 2);
@@ -216,6 +228,23 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     }
   }
 
+  if (KSPLIT) {
+    if (!producer) {
+      float* zp = zpart + (int64_t)blockIdx.z * Tn * d_R;
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int t = t0 + wn * 64 + b * 32 + n32;
+        if (t >= Tn) continue;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq)
+            *(float4*)(zp + (int64_t)t * d_R + r0 + wm * 64 + a * 32 + rq * 8 + hi * 4) =
+                make_float4(acc[a][b][rq * 4 + 0], acc[a][b][rq * 4 + 1], acc[a][b][rq * 4 + 2], acc[a][b][rq * 4 + 3]);
+      }
+    }
+    return;
+  }
   // ---- epilogue: SiLU in place, then W2 in chunks of up to 32 KV heads ---------------------------
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -264,6 +293,63 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   }
 }
 
+// scores[m][t] = sum_r SiLU(sum_z zpart[z][t][r]) W2[r][m] for the contraction-split launches: one workgroup per
+// token, thread i owns hidden units i, i + 256, ... (neighbouring lanes read neighbouring partials and
+// neighbouring rows of W2: few cache lines per load instruction), sums over the workgroup in LDS.  Fixed orders
+// throughout: deterministic.
+constexpr int FIN_THREADS = 256;
+__global__ __launch_bounds__(FIN_THREADS) void score_finish_kernel(const float* __restrict__ zpart, int n_z, int Tn,
+                                                                   int d_R, const float* __restrict__ W2f, int h_kv,
+                                                                   float* __restrict__ part, int part_T) {
+  __shared__ float red[FIN_THREADS / 64][8];
+  const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int m0 = 0; m0 < h_kv; m0 += 8) {
+    const int mc = min(8, h_kv - m0);
+    float p[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p[i] = 0.f;
+    const bool vec8 = mc == 8 && (h_kv & 3) == 0;          // a row's 8 weights as two aligned 16-byte loads
+    for (int r = tid; r < d_R; r += FIN_THREADS) {
+      float z = zpart[(int64_t)t * d_R + r];
+      for (int s = 1; s < n_z; ++s) z += zpart[((int64_t)s * Tn + t) * d_R + r];
+      const float a = z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(z * -1.4426950408889634f));
+      const float* w = W2f + (int64_t)r * h_kv + m0;
+      if (vec8) {
+        const float4 w0 = *(const float4*)w, w1 = *(const float4*)(w + 4);
+        p[0] = fmaf(a, w0.x, p[0]); p[1] = fmaf(a, w0.y, p[1]); p[2] = fmaf(a, w0.z, p[2]); p[3] = fmaf(a, w0.w, p[3]);
+        p[4] = fmaf(a, w1.x, p[4]); p[5] = fmaf(a, w1.y, p[5]); p[6] = fmaf(a, w1.z, p[6]); p[7] = fmaf(a, w1.w, p[7]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (i < mc) p[i] = fmaf(a, w[i], p[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int x = 32; x >= 1; x >>= 1) p[i] += __shfl_xor(p[i], x, 64);
+    }
+    __syncthreads();                                   // the previous chunk's sums have been read
+    if (lane == 0)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) red[wave][i] = p[i];
+    __syncthreads();
+    if (tid < mc) {
+      float sum = red[0][tid];
+      for (int w2 = 1; w2 < FIN_THREADS / 64; ++w2) sum += red[w2][tid];
+      part[(int64_t)(m0 + tid) * part_T + t] = sum;
+    }
+  }
+}
+
+// Floats of workspace for the partial pre-activations of contraction-split launches.
+constexpr int RT_ZROWS = 4096;     // token rows times slices at most
+size_t score_bf16_split_floats(const Dims& D, int chunk_max) {
+  if (score_parts_bf16(D) == 0 || D.d_R % 4 != 0) return 0;
+  const int rows = chunk_max < RT_ZROWS / 4 ? 4 * chunk_max : RT_ZROWS;
+  return (size_t)rows * D.d_R;
+}
+
 int score_parts_bf16(const Dims& D) {
   if (!D.bf16) return 0;
   // stages must not straddle q / k / v, and byte offsets inside one operand panel must fit 31 bits
@@ -272,11 +358,38 @@ int score_parts_bf16(const Dims& D) {
   return D.d_R / RT_M;
 }
 
-void launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T, const void* W1t,
-                       const float* W2f, float* part, hipStream_t st) {
+// Returns the number of partial score tensors written to `part` (the caller sums them): d_R / 128, or 1 when the
+// launch split the contraction (short chunks: at most a quarter as many 128 x 128 tiles as CUs; each slice keeps
+// at least 8 stages; LOCRET_SCORE_SPLIT, read per launch: 0 = never, k = k slices).  Measured on 32q/8kv x 128,
+// d_R = 1024: chunks of 1024 tokens (64 tiles, 4 slices) 49 -> 37 us; chunks of 2048 (128 tiles, 2 slices) gained
+// nothing in the head and cost attention 8 % (16 MB of partials through the L2), so two slices are not taken.
+int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T, const void* W1t,
+                      const float* W2f, float* part, hipStream_t st, float* zpart, size_t zpart_floats) {
   dim3 grid((T + RT_N - 1) / RT_N, D.d_R / RT_M);
-  hipLaunchKernelGGL(score_mfma_kernel, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T);
+  int n_z = 1;
+  if (zpart != nullptr) {
+    const char* e = getenv("LOCRET_SCORE_SPLIT");
+    const int forced = e ? atoi(e) : -1;
+    const int tiles = (int)(grid.x * grid.y), stages = D.K / RT_K;
+    n_z = forced >= 0 ? forced : (256 / tiles >= 4 ? 256 / tiles : 1);
+    n_z = n_z > 8 ? 8 : n_z;
+    auto last_empty = [&](int n) { return (n - 1) * ((stages + n - 1) / n) >= stages; };   // slices are ceil(stages / n) long
+    while (n_z > 1 && ((size_t)n_z * T * D.d_R > zpart_floats || (forced < 0 && stages / n_z < 8) || last_empty(n_z))) --n_z;
+    if (n_z < 1) n_z = 1;
+  }
+  if (n_z == 1) {
+    hipLaunchKernelGGL(score_mfma_kernel<false>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+                       (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T,
+                       (float*)nullptr, D.d_R);
+    return D.d_R / RT_M;
+  }
+  grid.z = n_z;
+  hipLaunchKernelGGL(score_mfma_kernel<true>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+                     (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T, zpart,
+                     D.d_R);
+  hipLaunchKernelGGL(score_finish_kernel, dim3(T), dim3(FIN_THREADS), 0, st, (const float*)zpart, n_z, T, D.d_R, W2f,
+                     D.h_kv, part, T);
+  return 1;
 }
 
 }  // namespace locret

@@ -155,6 +155,18 @@ def test_key_split_chosen_for_short_chunks_behind_a_long_cache():
     layer.close()
 
 
+@pytest.mark.parametrize("n_z", ["0", "2", "5", "8"])
+def test_contraction_split_of_the_retaining_head(n_z, monkeypatch):
+    # short chunks give the retaining head too few 128 x 128 tiles for the CUs; the launcher then slices the
+    # contraction and a second kernel sums the slices, applies SiLU and W2 (chosen by itself in most streams of
+    # this file).  LOCRET_SCORE_SPLIT (read per launch) forces the number of slices, 0 = never.
+    monkeypatch.setenv("LOCRET_SCORE_SPLIT", n_z)
+    for kw in (SMALL[4], SMALL[5], SMALL[6]):
+        w = synth.tiny(**kw)
+        layer, o, _ = _run_stream(w, teacher_forced=True)
+        layer.close()
+
+
 def test_selection_as_its_own_launch(monkeypatch):
     # by default the head_dim-128 attention launch carries the selection in its first workgroups;
     # LOCRET_FUSE_SELECT=0 (read per call) launches it separately: same kept indices either way
