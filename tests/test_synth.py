@@ -38,12 +38,17 @@ def test_bf16_rounding_matches_library_cast():
 
 def test_workload_table_matches_named_configs():
     W = synth.WORKLOADS
-    c1, c2, c3, c4, c5 = (W[k] for k in sorted(W))
+    c1, c2, c3, c4, c5 = (W[k] for k in sorted(W) if k.startswith("cfg"))
     assert (c1.h, c1.h_kv, c1.d, c1.N, c1.B, c1.b, c1.n_s, c1.d_in, c1.d_R) == (8, 2, 64, 4096, 512, 1024, 64, 1536, 256)
     assert (c2.h, c2.h_kv, c2.d, c2.N, c2.B, c2.b, c2.n_s, c2.d_in, c2.d_R) == (32, 8, 128, 32768, 2048, 6144, 2048, 6144, 1024)
     assert (c3.N, c3.B, c3.b, c3.n_s, c3.planted_frac, c3.planted_scale) == (131072, 4096, 16384, 2048, 0.01, 4.0)
     assert (c4.h, c4.h_kv, c4.d, c4.b, c4.n_s, c4.d_in, c4.theta) == (32, 32, 96, 8192, 1024, 9216, 10000.0)
     assert (c5.N, c5.n_chunks, c5.b, c5.n_s) == (1048576, 256, 8192, 2048)
+    # the paper's own inference settings (Appendix "Hyperparameters, Environment and Baselines": b, B, n_s per model)
+    pl, pp = W["paper_llama31_row"], W["paper_phi3_row"]
+    assert (pl.h, pl.h_kv, pl.d, pl.b, pl.B, pl.n_s) == (32, 8, 128, 16384, 1024, 2500)
+    assert (pp.h, pp.h_kv, pp.d, pp.b, pp.B, pp.n_s) == (32, 32, 96, 6000, 3072, 2500)
+    assert len(W) == 7
 
 
 def test_planted_positions_scale_keys_of_all_heads():
