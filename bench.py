@@ -26,7 +26,7 @@ PEAK_F32_TFLOPS = 157.3
 # HBM bytes of one steady-state attention launch, from the two rocprofv3 counter runs summarised in
 # profiles/chunk_step_cfg3_llama_128k_hbm_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors the calibration pass gave).  Only valid for the workload it was measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 243.6e6}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 249.7e6}
 
 
 def attention_flops(w, n_c, T):
@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg3_llama_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-head-budgets", action="store_true",
+                    help="skip the head-wise-budget leg (profiling runs: keeps the launch counts those of the chunk step)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB): the "
                          "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -220,7 +222,7 @@ def main():
 
     # ---- head-wise budgets (next row of the scope table): the same layer with a pyramid of budgets of the
     # same total, steady state (every head at its budget), against equal budgets measured the same way
-    if w.h_kv >= 2 and w.h_kv <= B.LOCRET_MAX_HEAD_BUDGETS:
+    if w.h_kv >= 2 and w.h_kv <= B.LOCRET_MAX_HEAD_BUDGETS and not args.no_head_budgets:
         def steady_ms(lay, n_fill, n_timed=20):
             qc, kc, vc = chunks[min(1, need - 1)]
             for _ in range(n_fill):
