@@ -13,6 +13,7 @@ The 1M-token streaming configuration drives the selection with seeded scores ins
 retaining head (the oracle's float64 MLP over 256 chunks would take minutes); the retaining head
 and attention are still sampled against the oracle there, and per-chunk latency must stay flat.
 """
+import dataclasses
 import os
 from concurrent.futures import ThreadPoolExecutor
 
@@ -34,8 +35,10 @@ def _sample_rows(T, rng):
     return np.array(sorted({r for r in fixed + extra if 0 <= r < T}))
 
 
-def _stream_teacher_forced(name, attn_chunks):
+def _stream_teacher_forced(name, attn_chunks, n_tokens=None):
     w = synth.WORKLOADS[name]
+    if n_tokens is not None:
+        w = dataclasses.replace(w, N=n_tokens)          # a prefix of the stream (tokens do not depend on N)
     layer, W1, W2 = make_layer(w)
     o = make_oracle(w, W1, W2)
     rng = np.random.default_rng(w.seed)
@@ -76,6 +79,17 @@ def test_config3_llama_128k_full():
 
 def test_config4_phi3_128k_full():
     _stream_teacher_forced("cfg4_phi3_128k", attn_chunks={0, 1, 2, 20, 31})
+
+
+def test_paper_llama31_row_launch_shape():
+    # the paper's Llama-3.1 setting (b = 16384, B = 1024, n_s = 2500 > B): the first 36 chunks; at this chunk size the
+    # attention launch splits the keys and the retaining head its contraction once the cache is long enough
+    _stream_teacher_forced("paper_llama31_row", attn_chunks={0, 1, 15, 16, 35}, n_tokens=36 * 1024)
+
+
+def test_paper_phi3_row_launch_shape():
+    # the paper's Phi-3 setting (32 MHA heads x 96, b = 6000, B = 3072, n_s = 2500): 6 chunks and a ragged seventh
+    _stream_teacher_forced("paper_phi3_row", attn_chunks={0, 1, 2, 5, 6}, n_tokens=6 * 3072 + 1000)
 
 
 def test_config5_stream_1m_flat_latency_and_parity():
