@@ -331,7 +331,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   void* qr = D.rope ? c->ws + c->L.qr : nullptr;
 
-  // the head_dim-128 attention kernel rotates the queries itself: no rotated copy is written or read
+  // the matrix-core attention kernels rotate the queries themselves: no rotated copy is written or read
   const bool fused_q = c->mfma_attn && attention_bf16_rotates_q(D);
   HeadLens hl_tmp;
   const HeadLens* hl = c->lens(&hl_tmp);      // per-head cache lengths before this chunk, or NULL
@@ -380,7 +380,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
     c->mark(2, 1, st);
   };
   bool ok = true;
-  // The selection depends on the scores only.  Where the attention launch can carry it (head_dim-128 kernel,
+  // The selection depends on the scores only.  Where the attention launch can carry it (direct-to-LDS kernel, head_dim 128 or 96,
   // few enough candidates for its register-resident form) the retaining head runs first and the selection
   // rides in the first workgroups of the attention launch; LOCRET_FUSE_SELECT=0 (read per call) keeps the
   // separate launch.

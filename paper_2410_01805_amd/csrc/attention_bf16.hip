@@ -435,8 +435,9 @@ static int attn_variant() {      // read on every launch (cheap), so a process c
   return v;
 }
 
-static bool dma_applies(const Dims& Dm) {
-  return attn_variant() >= 4 && Dm.d == 128 && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
+static bool dma_applies(const Dims& Dm) {      // a direct-to-LDS kernel serves this shape: "pp" head dims 128 and 96, "dma" 128
+  const int v = attn_variant();
+  return v >= 4 && (Dm.d == 128 || (v == 6 && Dm.d == 96)) && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
 }
 
 // true when launch_attention_bf16 hands its LaunchTimer to the kernel's own dispatch (every kernel here

@@ -1,4 +1,4 @@
-// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950, head_dim 128: the direct-to-LDS kernel
+// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950, head_dim 128 (and 96): the direct-to-LDS kernel
 // of attention_dma.hip with its two wavefronts per SIMD held in anti-phase.
 //
 // A wavefront's tile is a chain S (16 MFMAs) -> softmax (32 exp2 on the transcendental unit, ~640
@@ -45,8 +45,8 @@ typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int PP_D = 128;
-constexpr int PP_TILE_B = KT * PP_D * 2;       // 16 KB per operand tile
+constexpr int PP_ROWB = 256;                   // bytes of a key's row in LDS: 128 bf16; head_dim 96 leaves the last quarter unused
+constexpr int PP_TILE_B = KT * PP_ROWB;        // 16 KB per operand tile
 constexpr int PP_STAGE_B = 2 * PP_TILE_B;      // K then V
 constexpr int PP_NW = 8;
 constexpr int PP_KPRE = 4;                     // K fragments fetched ahead of the S block
@@ -63,7 +63,11 @@ constexpr int PP_SPLIT_TOKENS = 2048;          // token rows (times splits) the 
 // GENERAL = false is the common case: every KV head holds n_c_common units, one KV head per XCD, the whole key
 // range per workgroup (n_c_h, spread_arg, order, n_split_arg and part_arg are ignored, so nothing of head-wise
 // lengths, the spread launch order or the key split remains in its code).
-template <bool GENERAL>
+// D = 128 or 96.  The tile layout in LDS is that of 128 dims for both (rows of 256 bytes): with 96 dims the lanes
+// of a direct load that would fetch the last four 16-byte chunks of a row point outside the buffer instead and
+// bring zeros, which nothing reads; every fragment address stays as it is, S takes 6 contraction steps and O^T
+// has 3 blocks of 32 dims.
+template <int D, bool GENERAL>
 __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __restrict__ q, const float2* __restrict__ tab, const bf16_t* __restrict__ Kx,
                                                              const bf16_t* __restrict__ V, bf16_t* __restrict__ out,
                                                              int Tn, int h, int g, int cap, int n_c_common, float c_log2,
@@ -74,7 +78,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   float* const part = GENERAL ? part_arg : nullptr;
   const int spread = GENERAL ? spread_arg : 0;
   constexpr int NW = PP_NW;
-  constexpr int D = PP_D;
+  static_assert(D == 128 || D == 96, "head dims of this kernel");
   constexpr int NKS = D / 16;
   constexpr int NDB = D / 32;
   __shared__ __attribute__((aligned(1024))) unsigned char ring[4 * PP_STAGE_B];
@@ -203,8 +207,13 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   // ---- instructions w%4 + 4u, so (i & 3) is the same for all of them ----------------------------------
   const int w4 = wave & 3;
   const int l_row = lane >> 4, l_pos = lane & 15;
-  const int k_vo = w4 * 1024 + l_row * 256 + ((l_pos ^ l_row ^ (w4 << 2)) * 16);   // + u * 4096 (scalar offset)
-  const int v_vo = w4 * 1024 + l_row * 256 + ((l_pos ^ (l_row << 2)) * 16);
+  // the lane's LDS slot is row 4 i + l_row, position l_pos; the row's swizzle decides which chunk of the row in
+  // memory belongs there.  Memory rows are D * 2 bytes; instruction i = w4 + 4 u starts at row 16 u + 4 w4.
+  constexpr int NCH = D / 8;                     // 16-byte chunks of a row in memory
+  constexpr int OUTSIDE = 0x7ffff000;            // an offset no buffer reaches: the load brings zeros
+  const int k_ch = l_pos ^ l_row ^ (w4 << 2), v_ch = l_pos ^ (l_row << 2);
+  const int k_vo = k_ch < NCH ? (w4 * 4 + l_row) * (D * 2) + k_ch * 16 : OUTSIDE;   // + u * 16 rows (scalar offset)
+  const int v_vo = v_ch < NCH ? (w4 * 4 + l_row) * (D * 2) + v_ch * 16 : OUTSIDE;
   auto issue = [&](int tile, int stage) __attribute__((always_inline)) {
     const int tile_u = __builtin_amdgcn_readfirstlane(tile);
     const int left = __builtin_amdgcn_readfirstlane(max(n_keys_s - tile_u * KT, 0) * (D * 2));   // 0 past the end
@@ -216,12 +225,12 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = w4 + u * 4;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, (lds_ptr_t)(sb + i * 1024), 16, k_vo, u * 4096, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, (lds_ptr_t)(sb + i * 1024), 16, k_vo, u * (16 * D * 2), 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = w4 + u * 4;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, (lds_ptr_t)(sb + PP_TILE_B + i * 1024), 16, v_vo, u * 4096, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, (lds_ptr_t)(sb + PP_TILE_B + i * 1024), 16, v_vo, u * (16 * D * 2), 0, 0);
     }
   };
 
@@ -457,8 +466,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
 // out[t][j][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m) over the key splits of a row (t, j);
 // a split whose sum is 0 saw no key of that row.  A thread owns 4 elements of a row.
 __global__ __launch_bounds__(256) void attn_pp_merge_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
-                                                            int rows, int n_split) {
-  constexpr int D = PP_D;
+                                                            int rows, int n_split, int D) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid / (D / 4);
   const int e = (int)(gid % (D / 4)) * 4;
@@ -488,16 +496,18 @@ __global__ __launch_bounds__(256) void attn_pp_merge_kernel(const float* __restr
   *(uint2*)(out + row * D + e) = wd;
 }
 
+static bool pp_head_dim(int d) { return d == 128 || d == 96; }
+
 // Floats of workspace for the partial results of key-split launches (0: this shape never splits).
 size_t attention_pp_split_floats(const Dims& Dm, int chunk_max) {
-  if (Dm.d != PP_D || !Dm.bf16) return 0;
+  if (!pp_head_dim(Dm.d) || !Dm.bf16) return 0;
   const int tokens = chunk_max < PP_SPLIT_TOKENS / 2 ? 2 * chunk_max : PP_SPLIT_TOKENS;
-  return (size_t)tokens * Dm.h * (PP_D + 2);
+  return (size_t)tokens * Dm.h * (Dm.d + 2);
 }
 
 // `tab` non-null: q holds un-rotated queries and the kernel rotates them (table row n_c + t).
 bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
-  if (Dm.d != PP_D || (int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;
+  if (!pp_head_dim(Dm.d) || (int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;
   const int wseg = ((n_cand + PP_NW - 1) / PP_NW + 63) & ~63;
   return wseg <= PP_SEL_MAXR * 64;
 }
@@ -506,7 +516,7 @@ bool attention_pp_fuses_select(const Dims& Dm, int n_cand) {
 bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
                               int T, int n_c, float scale, hipStream_t st, const SelectArgs* sel,
                               const HeadLens* n_c_h, float* split_part, size_t split_floats) {
-  if (Dm.d != PP_D) return false;
+  if (!pp_head_dim(Dm.d)) return false;
   if ((int64_t)Dm.cap * Dm.d * 2 >= (1ll << 31)) return false;   // 32-bit byte offsets inside one head
   constexpr int NW = PP_NW;
   const int g = Dm.g;
@@ -535,7 +545,7 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
     int want = forced >= 0 ? forced : 256 / items;
     want = want > PP_MAX_SPLIT ? PP_MAX_SPLIT : want;
     const int min_tiles = (min_nc + 1 + KT - 1) / KT;
-    while (want > 1 && ((size_t)want * T * Dm.h * (PP_D + 2) > split_floats || (forced < 0 && min_tiles / want < 8))) --want;
+    while (want > 1 && ((size_t)want * T * Dm.h * (Dm.d + 2) > split_floats || (forced < 0 && min_tiles / want < 8))) --want;
     n_split = want < 1 ? 1 : want;
   }
   const int n_tt_eff = n_ttiles * n_split;
@@ -543,17 +553,20 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
   const int n_wg = spread ? n_hgroups * ((n_tt_eff + 7) / 8) * 8 : n_hgroups * n_tt_eff;
   float* part = n_split > 1 ? split_part : nullptr;
 #define LOCRET_PP_LAUNCH(SP)                                                                                          \
-  hipExtLaunchKernelGGL(attn_pp_kernel<SP>, dim3(n_sel + n_wg), dim3(NW * 64), 0, st, tm.start,                         \
+  do { if (Dm.d == 96) LOCRET_PP_LAUNCH_D(96, SP); else LOCRET_PP_LAUNCH_D(128, SP); } while (0)
+#define LOCRET_PP_LAUNCH_D(DD, SP)                                                                                    \
+  hipExtLaunchKernelGGL((attn_pp_kernel<DD, SP>), dim3(n_sel + n_wg), dim3(NW * 64), 0, st, tm.start,                   \
                         part ? nullptr : tm.stop, 0, (const bf16_t*)q, tab, (const bf16_t*)Kx, (const bf16_t*)V,        \
                         (bf16_t*)out, T, Dm.h, g, Dm.cap, n_c, c_log2, hpw, n_hgroups, n_tt_eff, sa, n_sel, hl, spread, \
                         longest_first(hl, Dm.h_kv), n_split, part)
   if (part || spread || hl.ragged) LOCRET_PP_LAUNCH(true); else LOCRET_PP_LAUNCH(false);
 #undef LOCRET_PP_LAUNCH
+#undef LOCRET_PP_LAUNCH_D
   if (part) {
     const int rows = T * Dm.h;
-    const int64_t threads = (int64_t)rows * (PP_D / 4);
+    const int64_t threads = (int64_t)rows * (Dm.d / 4);
     hipExtLaunchKernelGGL(attn_pp_merge_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, nullptr, tm.stop, 0,
-                          (const float*)part, (bf16_t*)out, rows, n_split);
+                          (const float*)part, (bf16_t*)out, rows, n_split, Dm.d);
   }
   return true;
 }

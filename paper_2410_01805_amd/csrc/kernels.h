@@ -122,7 +122,7 @@ bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, cons
                               const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
                               const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr,
                               float* split_part = nullptr, size_t split_floats = 0);
-// Floats of scratch the head_dim-128 kernel wants for launches that split the key range (short chunks);
+// Floats of scratch the direct-to-LDS attention kernel wants for launches that split the key range (short chunks);
 // 0 when the shape never splits.  Without the buffer it does not split.
 size_t attention_pp_split_floats(const Dims& D, int chunk_max);
 bool attention_pp_fuses_select(const Dims& D, int n_cand);

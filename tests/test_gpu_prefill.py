@@ -167,6 +167,16 @@ def test_contraction_split_of_the_retaining_head(n_z, monkeypatch):
         layer.close()
 
 
+@pytest.mark.parametrize("variant", ["w8", "w4", "qb2", "pipe"])
+def test_alternative_attention_kernels_head_dim_96(variant, monkeypatch):
+    # head_dim 96 runs on the direct-to-LDS kernel by default (its LDS rows padded to 128 dims); the
+    # register-staged forms stay selectable
+    monkeypatch.setenv("LOCRET_ATTN_VARIANT", variant)
+    w = synth.tiny(**SMALL[5])
+    layer, o, _ = _run_stream(w, teacher_forced=True)
+    layer.close()
+
+
 def test_selection_as_its_own_launch(monkeypatch):
     # by default the head_dim-128 attention launch carries the selection in its first workgroups;
     # LOCRET_FUSE_SELECT=0 (read per call) launches it separately: same kept indices either way
