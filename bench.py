@@ -206,7 +206,7 @@ def main():
         "input_gen_s": round(t_gen, 1),
     }
 
-    # ---- decode step (next row of the scope table): one generated token over the full budget ----------
+    # ---- decode step (Eq. 1 with B = 1): one generated token over the full budget ----------
     # the cache is at the budget after the timed region; 64 generated tokens, plain generation (no score)
     n_dec = min(64, w.B)
     q1 = chunks[0][0][:1].contiguous(); k1 = chunks[0][1][:1].contiguous(); v1 = chunks[0][2][:1].contiguous()
@@ -229,7 +229,7 @@ def main():
                             "achieved": round(dec_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                             "frac": round(dec_gbs / PEAK_HBM_GBS, 4), "timed": "append + split-K attention + merge"}
 
-    # ---- head-wise budgets (next row of the scope table): the same layer with a pyramid of budgets of the
+    # ---- head-wise budgets (one budget per KV head): the same layer with a pyramid of budgets of the
     # same total, steady state (every head at its budget), against equal budgets measured the same way
     if w.h_kv >= 2 and w.h_kv <= B.LOCRET_MAX_HEAD_BUDGETS and not args.no_head_budgets:
         def steady_ms(lay, n_fill, n_timed=20):
