@@ -427,12 +427,10 @@ int locret_decode_step(locret_ctx* c, const void* q, const void* k, const void* 
   const Dims& D = c->D;
   CacheBuf A = c->buf(c->cur);
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
-  void* qr = D.rope ? c->ws + c->L.qr : nullptr;
   HeadLens hl_tmp;
-  launch_append(D, q, k, v, 1, c->n_c, c->seen, A, qr, tab, st, /*mark_unscored=*/!with_score, c->lens(&hl_tmp));
   if (with_score) run_score(c, q, k, v, 1, A.S, c->n_c, scores_out, st);
-  launch_decode_attention(D, D.rope ? qr : q, D.rope ? A.Kr : A.K, A.V, attn_out, c->n_c + 1, c->scale,
-                          (float*)(c->ws + c->L.dpart), st, c->lens(&hl_tmp, 1));
+  launch_decode_step(D, q, k, v, A, tab, attn_out, c->n_c, c->seen, c->scale, (float*)(c->ws + c->L.dpart), st,
+                     /*mark_unscored=*/!with_score, c->lens(&hl_tmp));
   grow(c, 1);
   c->seen += 1;
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;

@@ -10,6 +10,12 @@
 // probability and accumulate p * v for their dims.  Online softmax with a lazily raised max as in
 // the prefill kernels, one decision per UN rows.  The (max, sum, vector) triples of the 16 or 32
 // row slots of a workgroup are merged through LDS, those of the splits by decode_merge_kernel.
+//
+// The step is two launches.  The split kernel goes over the units already in the cache and rotates the
+// (un-rotated) query itself; one more workgroup per KV head takes the new token: one more partial (logit from
+// the rotated query and key, value row, sum 1) and the append to the cache (K, V, the rotated-key shadow, the
+// original position, and a NaN score when the caller does not score generated tokens).  The merge kernel
+// combines the partials.  A separate append launch cost 15 % of the step.
 #include <stdlib.h>
 
 #include "device_util.h"
@@ -24,12 +30,32 @@ constexpr float DEC_RESCALE_LOG2 = 8.f;
 template <int X> struct Pow2Ceil { static constexpr int value = X <= 1 ? 1 : 2 * Pow2Ceil<(X + 1) / 2>::value; };
 template <> struct Pow2Ceil<1> { static constexpr int value = 1; };
 
+// The new token of a decode step and where it goes (all device pointers; q, k, v un-rotated).
+struct DecodeToken {
+  const void* q;          // [h][d]
+  const void* k;          // [h_kv][d]
+  const void* v;          // [h_kv][d]
+  const float2* tab;      // rotary table, or NULL
+  void* K;                // cache arrays of the live copy
+  void* V;
+  void* Kr;
+  float* S;
+  int32_t* P;
+  int g, cap, n_c, seen, mark_unscored;
+  float c_log2;
+  HeadLens n_c_h;         // units per head before the token (ragged), else n_c
+};
+
 template <typename T, int D, int G>
-__global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __restrict__ q, const T* __restrict__ Kx,
-                                                                  const T* __restrict__ V, int g, int g0, int cap,
-                                                                  int n_keys_common, int keys_per_wg, float c_log2,
-                                                                  float* __restrict__ part, int n_splits,
-                                                                  HeadLens n_keys_h) {
+__global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __restrict__ Kx, int g0, int keys_per_wg,
+                                                                  float* __restrict__ part, DecodeToken tk) {
+  // n_splits partials per query head: gridDim.x - 1 splits over the cached units, then the new token's, which the
+  // last workgroup of a head forms (it has no units of its own, so it is done long before the others)
+  const T* __restrict__ q = (const T*)tk.q;
+  const T* __restrict__ V = (const T*)tk.V;
+  const float2* __restrict__ tab = tk.tab;
+  const int g = tk.g, cap = tk.cap, n_splits = (int)gridDim.x;
+  const float c_log2 = tk.c_log2;
   constexpr int VEC = Vec16<T>::N;
   constexpr int LPR = D / VEC;                       // lanes that hold data of one row
   constexpr int LPRP = Pow2Ceil<LPR>::value;         // lanes reserved per row
@@ -46,21 +72,52 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
   const bool act = sub < LPR;
   // head-wise budgets: a head shorter than the longest leaves its last splits empty (k1 <= k0: no row is
   // read, the partial carries max -inf and sum 0, which the merge weighs with 0)
-  const int n_keys = head_len(n_keys_h, m, n_keys_common);
+  const int n_keys = head_len(tk.n_c_h, m, tk.n_c);   // units of this head in the cache = the new token's slot and position
   const int k0 = split * keys_per_wg;
   const int k1 = min(n_keys, k0 + keys_per_wg);
   const T* Kb = Kx + (int64_t)m * cap * D;
   const T* Vb = V + (int64_t)m * cap * D;
   const int off = (act ? sub : 0) * VEC;
 
+  // `tab` non-null: q is un-rotated and takes position n_keys (the slot the token is appended at).  One thread
+  // per 16-byte chunk of the G query rows rotates its dims with the partner dims (+- D/2), rounds to the storage
+  // type as the rotated query of a chunk is, and leaves the row in LDS for the whole workgroup: every workgroup
+  // of the launch reads the same few lines of q and of the table, and those requests queue on one L2 channel
+  // (with every lane rotating for itself the kernel took 26 us instead of 20).
   float qv[G][VEC];
+  __shared__ float qs[G * D];
+  if (tab != nullptr) {
+    constexpr int CPR = D / VEC;                       // chunks per row
+    if (tid < G * CPR) {
+      const int u = tid / CPR, offc = (tid % CPR) * VEC;
+      const int j = m * g + min(g0 + u, g - 1);
+      const bool low = offc < D / 2;
+      V16 x, y;
+      x.raw = *(const raw_t*)(q + (int64_t)j * D + offc);
+      y.raw = *(const raw_t*)(q + (int64_t)j * D + (low ? offc + D / 2 : offc - D / 2));
+      const float2* tr = tab + (int64_t)n_keys * (D / 2) + (low ? offc : offc - D / 2);
 #pragma unroll
-  for (int u = 0; u < G; ++u) {
-    const int j = m * g + min(g0 + u, g - 1);        // spare heads repeat the last one (not written)
-    V16 x;
-    x.raw = *(const raw_t*)(q + (int64_t)j * D + off);
+      for (int e = 0; e < VEC; ++e) {
+        const float2 cs = tr[e];
+        V16 r;
+        r.set(0, low ? x.get(e) * cs.x - y.get(e) * cs.y : x.get(e) * cs.x + y.get(e) * cs.y);
+        qs[u * D + offc + e] = r.get(0) * c_log2;      // logits in log2 units
+      }
+    }
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) qv[u][e] = act ? x.get(e) * c_log2 : 0.f;   // logits in log2 units
+    for (int u = 0; u < G; ++u)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) qv[u][e] = act ? qs[u * D + off + e] : 0.f;
+  } else {
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      const int j = m * g + min(g0 + u, g - 1);        // spare heads repeat the last one (not written)
+      V16 x;
+      x.raw = *(const raw_t*)(q + (int64_t)j * D + off);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) qv[u][e] = act ? x.get(e) * c_log2 : 0.f;   // logits in log2 units
+    }
   }
   float o[G][VEC], mrun[G], lrun[G];
 #pragma unroll
@@ -145,7 +202,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < G * PW; idx += DEC_THREADS) {
+  const bool token_wg = split == n_splits - 1;
+  for (int idx = tid; idx < G * PW && !token_wg; idx += DEC_THREADS) {
     const int u = idx / PW, e = idx % PW;
     if (g0 + u >= g) continue;
     float M = -INFINITY;
@@ -164,6 +222,64 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
     }
     const int j = m * g + g0 + u;
     part[((int64_t)j * n_splits + split) * PW + e] = val;
+  }
+
+  // ---- the new token (last workgroup of the head): its partial for the G heads, and the append ------------------
+  if (!token_wg) return;
+  __shared__ float ks[D];                              // its key, rotated to position n_keys and rounded as stored
+  __shared__ float dots[G][DEC_THREADS / 64];
+  if (tid < D) {
+    const T* kp = (const T*)tk.k + (int64_t)m * D;
+    float ke = Elem<T>::ld(kp + tid);
+    if (tab != nullptr) {
+      const bool low = tid < D / 2;
+      const float kpar = Elem<T>::ld(kp + (low ? tid + D / 2 : tid - D / 2));
+      const float2 cs = tab[(int64_t)n_keys * (D / 2) + (low ? tid : tid - D / 2)];
+      ke = low ? ke * cs.x - kpar * cs.y : ke * cs.x + kpar * cs.y;
+      T rounded;
+      Elem<T>::st(&rounded, ke);
+      ke = Elem<T>::ld(&rounded);
+    }
+    ks[tid] = ke;
+    if (g0 == 0) {                                     // one launch per step appends
+      const int64_t row = ((int64_t)m * cap + n_keys) * D + tid;
+      ((T*)tk.K)[row] = kp[tid];
+      ((T*)tk.V)[row] = ((const T*)tk.v)[(int64_t)m * D + tid];
+      if (tab != nullptr) Elem<T>::st((T*)tk.Kr + row, ke);
+      if (tid == 0) {
+        tk.P[(int64_t)m * cap + n_keys] = tk.seen;
+        if (tk.mark_unscored) tk.S[(int64_t)m * cap + n_keys] = __uint_as_float(0x7fc00000u);   // NaN: ranks last
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    float pr = 0.f;
+    if (tid < D) {
+      const int j = m * g + min(g0 + u, g - 1);
+      const float qe = tab != nullptr ? qs[u * D + tid] : Elem<T>::ld(q + (int64_t)j * D + tid) * c_log2;
+      pr = qe * ks[tid];
+    }
+#pragma unroll
+    for (int x = 32; x >= 1; x >>= 1) pr += __shfl_xor(pr, x, 64);
+    if (lane == 0) dots[u][wave] = pr;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * PW; idx += DEC_THREADS) {
+    const int u = idx / PW, e = idx % PW;
+    if (g0 + u >= g) continue;
+    float val;
+    if (e < D) {
+      val = Elem<T>::ld((const T*)tk.v + (int64_t)m * D + e);
+    } else if (e == D) {
+      val = 0.f;
+      for (int w2 = 0; w2 < (D + 63) / 64; ++w2) val += dots[u][w2];     // the wavefronts that hold dims, in order
+    } else {
+      val = 1.f;
+    }
+    const int j = m * g + g0 + u;
+    part[((int64_t)j * n_splits + n_splits - 1) * PW + e] = val;
   }
 }
 
@@ -232,39 +348,42 @@ int decode_keys_per_split() {
   return v;
 }
 
-int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() - 1) / decode_keys_per_split(); }
+// partials per query head at most: the splits over a full cache and the new token's
+int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() - 1) / decode_keys_per_split() + 1; }
 
 template <typename T, int DD>
-static void decode_launch(const Dims& D, const T* q, const T* Kx, const T* V, T* out, int n_keys, float scale,
-                          float* part, hipStream_t st, const HeadLens& hl) {
+static void decode_launch(const Dims& D, const DecodeToken& tk, T* out, float* part, hipStream_t st) {
   const int kpw = decode_keys_per_split();
-  const int n_splits = (n_keys + kpw - 1) / kpw;
-  const float c_log2 = scale * 1.4426950408889634f;
-  const dim3 grid(n_splits, D.h_kv);
+  const int n_attn = (tk.n_c + kpw - 1) / kpw;            // splits over the units already in the cache (the longest head's)
+  const T* Kx = (const T*)(D.rope ? tk.Kr : tk.K);
+  const dim3 grid(n_attn + 1, D.h_kv);                    // + the workgroup of the new token
   for (int g0 = 0; g0 < D.g; g0 += 4) {
     const int left = D.g - g0;
     if (left >= 3)
-      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 4>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits, hl);
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 4>), grid, dim3(DEC_THREADS), 0, st, Kx, g0, kpw, part, tk);
     else if (left == 2)
-      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 2>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits, hl);
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 2>), grid, dim3(DEC_THREADS), 0, st, Kx, g0, kpw, part, tk);
     else
-      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, q, Kx, V, D.g, g0, D.cap, n_keys,
-                         kpw, c_log2, part, n_splits, hl);
+      hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, Kx, g0, kpw, part, tk);
   }
-  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, part, n_splits, D.d, out);
+  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, (const float*)part, n_attn + 1, D.d,
+                     out);
 }
 
-void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
-                             float scale, float* part, hipStream_t st, const HeadLens* n_keys_h) {
-  const HeadLens hl = head_lens_or_common(n_keys_h);
-#define LOCRET_DEC(DD)                                                                                              \
-  case DD:                                                                                                          \
-    if (D.bf16) decode_launch<bf16_t, DD>(D, (const bf16_t*)q, (const bf16_t*)Kx, (const bf16_t*)V, (bf16_t*)out,  \
-                                          n_keys, scale, part, st, hl);                                        \
-    else decode_launch<float, DD>(D, (const float*)q, (const float*)Kx, (const float*)V, (float*)out, n_keys,      \
-                                  scale, part, st, hl);                                                             \
+void launch_decode_step(const Dims& D, const void* q, const void* k, const void* v, const CacheBuf& c,
+                        const float2* tab, void* out, int n_c, int64_t seen, float scale, float* part, hipStream_t st,
+                        bool mark_unscored, const HeadLens* n_c_h) {
+  DecodeToken tk;
+  tk.q = q; tk.k = k; tk.v = v;
+  tk.tab = D.rope ? tab : nullptr;
+  tk.K = c.K; tk.V = c.V; tk.Kr = c.Kr; tk.S = c.S; tk.P = c.P;
+  tk.g = D.g; tk.cap = D.cap; tk.n_c = n_c; tk.seen = (int)seen; tk.mark_unscored = mark_unscored ? 1 : 0;
+  tk.c_log2 = scale * 1.4426950408889634f;
+  tk.n_c_h = head_lens_or_common(n_c_h);
+#define LOCRET_DEC(DD)                                                                  \
+  case DD:                                                                              \
+    if (D.bf16) decode_launch<bf16_t, DD>(D, tk, (bf16_t*)out, part, st);               \
+    else decode_launch<float, DD>(D, tk, (float*)out, part, st);                        \
     break;
   switch (D.d) {
     LOCRET_DEC(16)

@@ -140,13 +140,15 @@ bool attention_bf16_rotates_q(const Dims& D);
 // True when launch_attention_bf16 attaches the LaunchTimer's events to the attention kernel's dispatch.
 bool attention_bf16_attaches_timer(const Dims& D);
 
-// Decode step (Eq. 1 with B = 1): one query row per head (rotated if rope) over slots [0, n_keys)
-// (n_keys_h: per KV head, n_keys then being the largest).
+// Decode step (Eq. 1 with B = 1): the token q [h][d], k, v [h_kv][d] (un-rotated) attends over the n_c units of
+// cache copy `c` and itself at position n_c, and is appended at slot n_c (K, V, rotated K, P = seen; with
+// mark_unscored a NaN score).  n_c_h: units per KV head, n_c then being the largest.
 // `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.
 int decode_keys_per_split();
 int decode_max_splits(const Dims& D);
-void launch_decode_attention(const Dims& D, const void* q, const void* Kx, const void* V, void* out, int n_keys,
-                             float scale, float* part, hipStream_t st, const HeadLens* n_keys_h = nullptr);
+void launch_decode_step(const Dims& D, const void* q, const void* k, const void* v, const CacheBuf& c,
+                        const float2* tab, void* out, int n_c, int64_t seen, float scale, float* part, hipStream_t st,
+                        bool mark_unscored, const HeadLens* n_c_h = nullptr);
 
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.
