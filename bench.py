@@ -227,7 +227,7 @@ def main():
     dec_gbs = dec_bytes / (dec_ms * 1e-3) / 1e9
     extra["decode_step"] = {"units": n_units, "ms_per_token": round(dec_ms, 4), "bound": "hbm",
                             "achieved": round(dec_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4), "timed": "append + split-K attention + merge"}
+                            "frac": round(dec_gbs / PEAK_HBM_GBS, 4), "timed": "split-K attention (rotates the query, appends the token) + merge"}
 
     # ---- head-wise budgets (one budget per KV head): the same layer with a pyramid of budgets of the
     # same total, steady state (every head at its budget), against equal budgets measured the same way
