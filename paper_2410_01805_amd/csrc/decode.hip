@@ -338,22 +338,39 @@ __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const f
   }
 }
 
-int decode_keys_per_split() {
-  static int v = 0;
-  if (v == 0) {
+// Keys per split.  LOCRET_DEC_KEYS (read once; a multiple of 64 in 64 .. 65536) fixes it; otherwise it is chosen per
+// launch so that the launch has about 700 workgroups (2.7 per CU), but never under 128 keys, in steps of 64.
+// Measured per token, end to end: 8 heads x 16.6K units 24.0 us at 192 keys (25.4 at 256), 32 heads x 8.4K units
+// 21.5 us at 384 (22.6 at 256), 8 heads x 6.4K units 14.7 us at 128 (18.6 at 64, 15.6 at 256).
+constexpr int DEC_KEYS_MIN = 128;
+static int decode_keys_env() {
+  static int v = -1;
+  if (v < 0) {
     const char* e = getenv("LOCRET_DEC_KEYS");
     const int x = e ? atoi(e) : 0;
-    v = (x >= 64 && x <= 65536 && x % 64 == 0) ? x : 256;
+    v = (x >= 64 && x <= 65536 && x % 64 == 0) ? x : 0;
   }
   return v;
 }
 
-// partials per query head at most: the splits over a full cache and the new token's
-int decode_max_splits(const Dims& D) { return (D.cap + decode_keys_per_split() - 1) / decode_keys_per_split() + 1; }
+int decode_keys_per_split(const Dims& D, int n_keys) {
+  if (decode_keys_env() > 0) return decode_keys_env();
+  const int64_t want = ((int64_t)D.h_kv * n_keys + 703) / 704;
+  int k = (int)((want + 63) / 64 * 64);
+  if (k < DEC_KEYS_MIN) k = DEC_KEYS_MIN;
+  if (k > 65536) k = 65536;
+  return k;
+}
+
+// partials per query head at most: the splits over a full cache at the smallest split size, and the new token's
+int decode_max_splits(const Dims& D) {
+  const int kmin = decode_keys_env() > 0 ? decode_keys_env() : DEC_KEYS_MIN;
+  return (D.cap + kmin - 1) / kmin + 1;
+}
 
 template <typename T, int DD>
 static void decode_launch(const Dims& D, const DecodeToken& tk, T* out, float* part, hipStream_t st) {
-  const int kpw = decode_keys_per_split();
+  const int kpw = decode_keys_per_split(D, tk.n_c);
   const int n_attn = (tk.n_c + kpw - 1) / kpw;            // splits over the units already in the cache (the longest head's)
   const T* Kx = (const T*)(D.rope ? tk.Kr : tk.K);
   const dim3 grid(n_attn + 1, D.h_kv);                    // + the workgroup of the new token

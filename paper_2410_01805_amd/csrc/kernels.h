@@ -144,7 +144,7 @@ bool attention_bf16_attaches_timer(const Dims& D);
 // cache copy `c` and itself at position n_c, and is appended at slot n_c (K, V, rotated K, P = seen; with
 // mark_unscored a NaN score).  n_c_h: units per KV head, n_c then being the largest.
 // `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.
-int decode_keys_per_split();
+int decode_keys_per_split(const Dims& D, int n_keys);
 int decode_max_splits(const Dims& D);
 void launch_decode_step(const Dims& D, const void* q, const void* k, const void* v, const CacheBuf& c,
                         const float2* tab, void* out, int n_c, int64_t seen, float scale, float* part, hipStream_t st,

@@ -65,6 +65,18 @@ def _stream_teacher_forced(name, attn_chunks, n_tokens=None):
         np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
         np.testing.assert_array_equal(host(V[m]), o.V[m].astype(np.float32))
         np.testing.assert_array_equal(S[m].cpu().numpy().view(np.uint32), o.S[m].view(np.uint32))
+    # two generated tokens on the full cache (the split sizes and counts of the decode step at this size)
+    for i in range(2):
+        q, k, v = synth.tokens(w, w.N + i, w.N + i + 1)
+        out_ref, sc_ref, _ = o.prefill_chunk(q, k, v, 0, evict=False)
+        out, sc = layer.decode_step(dev(q, w), dev(k, w), dev(v, w), with_score=True)
+        assert_close(host(out), out_ref, w.dtype, f"{name} decode {i} attention", per_row=True, kappa=w.planted_scale)
+        assert_close(sc.cpu().numpy(), sc_ref[:, 0], w.dtype, f"{name} decode {i} score")
+    K, V, S, P = layer.cache_tensors()
+    for m in range(w.h_kv):
+        np.testing.assert_array_equal(P[m].cpu().numpy(), o.P[m])
+        np.testing.assert_array_equal(host(K[m]), o.K[m].astype(np.float32))
+        np.testing.assert_array_equal(host(V[m]), o.V[m].astype(np.float32))
     layer.close()
 
 
