@@ -26,7 +26,7 @@ PEAK_F32_TFLOPS = 157.3
 # HBM bytes of one steady-state attention launch, from the two rocprofv3 counter runs summarised in
 # profiles/chunk_step_cfg3_llama_128k_hbm_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors the calibration pass gave).  Only valid for the workload it was measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 249.7e6}
+MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 249.6e6}
 
 
 def attention_flops(w, n_c, T):
