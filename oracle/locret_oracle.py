@@ -39,7 +39,8 @@ Parity pins (tests/test_oracle_*.py): brute-force dense masked attention written
 with Python loops, a library SDPA for the never-evicting case, sliding-window
 special case, closed-form kept sets, the two cache-problem conditions of
 Appendix "Causal Importance Score Simulates a Cache Problem", a triple-loop MLP,
-and the bookkeeping numbers the paper prints (tests/golden/).
+the bookkeeping numbers the paper prints (tests/golden/), and for head-wise budgets
+the closed form and the brute force applied head by head.
 """
 from __future__ import annotations
 
