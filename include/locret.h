@@ -49,6 +49,7 @@ extern "C" {
                                 cache would overflow its capacity)                         */
 #define LOCRET_EHIP     -5   /* the HIP runtime reported an error                          */
 #define LOCRET_ENOMEM   -6   /* workspace too small / host allocation failed               */
+#define LOCRET_ELIMIT   -7   /* size beyond the fixed scratch of locret_score_static       */
 
 #define LOCRET_F32   0
 #define LOCRET_BF16  1
@@ -151,6 +152,24 @@ int locret_decode_step(locret_ctx* ctx, const void* q, const void* k, const void
 /* Retaining head alone (Section 3.3): scores[m][t] for T tokens; the cache is not touched. */
 int locret_score(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t T,
                  float* scores, void* stream);
+
+/* locret_score for callers that cannot allocate device memory or hand over a workspace region for scratch:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical scores, but the kernels' scratch (partial scores per block of 128 hidden units,
+ * and for short chunks the partial pre-activations of a split contraction) lies in a fixed array that is
+ * part of the library's device code: 20 MiB per GPU that runs the library, held until the process ends,
+ * looked up once per device in locret_create.  The call allocates nothing and frees nothing.
+ * Limit: blocks * n_kv_heads * T <= LOCRET_STATIC_PART_FLOATS with blocks = d_hidden / 128 on the matrix-core path
+ * (bf16, d_hidden a multiple of 128) and d_hidden / 64 rounded up otherwise,
+ * else LOCRET_ELIMIT and nothing is launched (the five named configurations fit at their chunk sizes).  Short
+ * chunks split the contraction as locret_score does as long as the slices fit 4 Mi floats; beyond that they run
+ * unsplit (same scores up to summation order).
+ * Every call on a GPU, from any context, shares that GPU's array and nothing in it has to start at zero (a call
+ * writes every element before reading it): calls that overlap in time on one GPU (two streams, two threads)
+ * race and must be ordered by the caller.  LOCRET_ESTATE if the context was created on a device index >= 64. */
+#define LOCRET_STATIC_PART_FLOATS (1u << 20)
+int locret_score_static(locret_ctx* ctx, const void* q, const void* k, const void* v, int32_t T,
+                        float* scores, void* stream);
 
 /* Append + stabilizer-masked top-b + compaction alone (Section 3.4, Algorithm 1) on caller-supplied
  * scores [n_kv_heads][T]; arguments as in locret_prefill_chunk. */

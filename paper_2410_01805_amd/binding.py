@@ -17,14 +17,14 @@ import torch  # noqa: F401  (memory and streams come from here as well)
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "liblocret.so")
 
-LOCRET_OK, LOCRET_EINVAL, LOCRET_ESHAPE, LOCRET_EALIGN, LOCRET_ESTATE, LOCRET_EHIP, LOCRET_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+LOCRET_OK, LOCRET_EINVAL, LOCRET_ESHAPE, LOCRET_EALIGN, LOCRET_ESTATE, LOCRET_EHIP, LOCRET_ENOMEM, LOCRET_ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 LOCRET_F32, LOCRET_BF16 = 0, 1
 
 EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_set_pinned_prefix", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
     "locret_destroy", "locret_strerror", "locret_profile_mode", "locret_profile_enable", "locret_profile_read",
-    "locret_set_head_budgets", "locret_cache_lens",
+    "locret_set_head_budgets", "locret_cache_lens", "locret_score_static",
 ]
 LOCRET_PROF_STAGES = 5
 LOCRET_MAX_HEAD_BUDGETS = 64
@@ -57,6 +57,8 @@ def _load() -> C.CDLL:
     lib.locret_prefill_chunk.argtypes = [vp, vp, vp, vp, i32, i32, i32, f32p, vp, f32p, i32p, vp]
     lib.locret_score.restype = C.c_int
     lib.locret_score.argtypes = [vp, vp, vp, vp, i32, f32p, vp]
+    lib.locret_score_static.restype = C.c_int
+    lib.locret_score_static.argtypes = [vp, vp, vp, vp, i32, f32p, vp]
     lib.locret_decode_step.restype = C.c_int
     lib.locret_decode_step.argtypes = [vp, vp, vp, vp, i32, vp, f32p, vp]
     lib.locret_evict_compact.restype = C.c_int
@@ -180,6 +182,11 @@ def locret_decode_step(ctx, q, k, v, with_score, attn_out, scores_out=None, stre
 
 def locret_score(ctx, q, k, v, T, scores, stream=None) -> None:
     _check(lib.locret_score(ctx, _ptr(q), _ptr(k), _ptr(v), T, _ptr(scores), _stream(stream)), "locret_score")
+
+
+def locret_score_static(ctx, q, k, v, T, scores, stream=None) -> None:
+    _check(lib.locret_score_static(ctx, _ptr(q), _ptr(k), _ptr(v), T, _ptr(scores), _stream(stream)),
+           "locret_score_static")
 
 
 def locret_evict_compact(ctx, chunk_scores, k_chunk, v_chunk, T, n_stab, kept_idx_out, stream=None) -> None:

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -88,6 +89,36 @@ void make_layout(const locret_config* c, const Dims& D, Layout* L) {
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// ---- scratch of the entry point that allocates nothing (locret_score_static) ------------------------------
+// Device memory that lives with the code object: every GPU that loads the library holds its own copy, at its
+// own address, until the process ends.  First the partial scores part[blocks][h_kv][T], then the partial
+// pre-activations of launches that split the contraction.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; kernels and launchers get the looked-up address.
+constexpr size_t STATIC_PART_FLOATS = LOCRET_STATIC_PART_FLOATS;     // 4 MiB
+constexpr size_t STATIC_ZPART_FLOATS = (size_t)4 << 20;              // 16 MiB
+static __device__ __align__(256) float scratch[STATIC_PART_FLOATS + STATIC_ZPART_FLOATS];
+
+constexpr int MAX_DEVICES = 64;
+float* g_scratch_ptr[MAX_DEVICES];     // per device: address of that device's copy, NULL until looked up
+std::mutex g_scratch_mu;
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+int scratch_of_current_device(int* device, float** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return LOCRET_EHIP; }
+  *device = dev;
+  *ptr = nullptr;
+  if (dev < 0 || dev >= MAX_DEVICES) return LOCRET_OK;          // the static entry point then reports LOCRET_ESTATE
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return LOCRET_EHIP; }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return LOCRET_OK;
+}
+
 }  // namespace
 
 struct locret_ctx {
@@ -95,6 +126,8 @@ struct locret_ctx {
   Dims D;
   Layout L;
   char* ws;
+  int device;       // the device that was current at locret_create (the workspace's)
+  float* scratch;   // that device's copy of the static scratch array, or NULL
   int cur;          // live cache copy
   int n_c;          // units per head in the live copy
   int64_t seen;     // tokens appended so far
@@ -170,6 +203,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   if (bytes < c->L.total) { delete c; return LOCRET_ENOMEM; }
   c->ws = (char*)ws;
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  if (scratch_of_current_device(&c->device, &c->scratch) != LOCRET_OK) { delete c; return LOCRET_EHIP; }
   const char* force = getenv("LOCRET_FORCE_SIMPLE");
   const bool simple = force && force[0] == '1';
   const int d = cfg->head_dim;
@@ -240,14 +274,21 @@ int locret_reset(locret_ctx* c) {
 }
 
 // reduce = false: only the partial scores are formed (ws + L.part, *n_parts of them); the caller sums them
+// part / zpart: where the partial scores and (split launches) partial pre-activations go; NULL part = the
+// workspace's buffers
 static void run_score(locret_ctx* c, const void* q, const void* k, const void* v, int T, float* S_dst, int n_c,
-                      float* out, hipStream_t st, bool reduce = true, int* n_parts = nullptr) {
+                      float* out, hipStream_t st, bool reduce = true, int* n_parts = nullptr, float* part = nullptr,
+                      float* zpart = nullptr, size_t zpart_floats = 0) {
   HeadLens hl_tmp;
-  float* part = (float*)(c->ws + c->L.part);
+  if (!part) {
+    part = (float*)(c->ws + c->L.part);
+    zpart = c->L.zpart_floats ? (float*)(c->ws + c->L.zpart) : nullptr;
+    zpart_floats = c->L.zpart_floats;
+  }
   int parts;
   if (c->mfma_score) {
     parts = launch_score_bf16(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st,
-                              c->L.zpart_floats ? (float*)(c->ws + c->L.zpart) : nullptr, c->L.zpart_floats);
+                              zpart_floats ? zpart : nullptr, zpart_floats);
   } else {
     launch_score_simple(c->D, q, k, v, T, c->ws + c->L.W1t, (const float*)(c->ws + c->L.W2f), part, st);
     parts = score_parts_simple(c->D);
@@ -446,6 +487,21 @@ int locret_score(locret_ctx* c, const void* q, const void* k, const void* v, int
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
 }
 
+int locret_score_static(locret_ctx* c, const void* q, const void* k, const void* v, int32_t T, float* scores,
+                        void* stream) {
+  if (!c || !q || !k || !v || !scores) return LOCRET_EINVAL;
+  if (T < 1 || T > c->cfg.chunk_max) return LOCRET_ESHAPE;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(scores)) return LOCRET_EALIGN;
+  if (!c->have_weights || !c->scratch) return LOCRET_ESTATE;
+  const int parts = c->mfma_score ? score_parts_bf16(c->D) : score_parts_simple(c->D);     // of the kernel that will run
+  if ((size_t)parts * c->D.h_kv * (size_t)T > STATIC_PART_FLOATS) return LOCRET_ELIMIT;
+  // the launcher splits the contraction exactly as locret_score does while the slices fit the static region
+  const size_t zf = c->L.zpart_floats < STATIC_ZPART_FLOATS ? c->L.zpart_floats : STATIC_ZPART_FLOATS;
+  run_score(c, q, k, v, T, nullptr, 0, scores, (hipStream_t)stream, true, nullptr, c->scratch,
+            c->scratch + STATIC_PART_FLOATS, zf);
+  return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
+}
+
 int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k, const void* v, int32_t T,
                          int32_t n_stab, int32_t* kept_idx_out, void* stream) {
   if (!c || !chunk_scores || !k || !v) return LOCRET_EINVAL;
@@ -557,6 +613,7 @@ const char* locret_strerror(int code) {
     case LOCRET_ESTATE: return "call not valid in this state (weights not set, or cache capacity exceeded)";
     case LOCRET_EHIP: return "HIP runtime error";
     case LOCRET_ENOMEM: return "workspace too small or host allocation failed";
+    case LOCRET_ELIMIT: return "size beyond the static scratch of the entry point that allocates nothing";
     default: return "unknown error code";
   }
 }
