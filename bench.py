@@ -2,10 +2,13 @@
 """Benchmark of the Locret chunk step on one MI355X.
 
 A step is one locret_prefill_chunk call (attention + retaining head + select + compact) on one
-chunk of the synthetic 128K-token stream; the timed region is K consecutive chunks starting from
-an empty cache (K = all 32 chunks by default, so `value` is whole-stream prefill tokens/s per
-layer at 131072 tokens).  Inputs are generated on the host from the seeded recipe and are resident
-in HBM before the clock starts.  Prints ONE JSON line.
+chunk of the synthetic 128K-token stream.  The timed region is exactly K consecutive steps that start
+from an empty cache at chunk 0 and wrap to a new pass (empty cache again) after the last chunk; K
+defaults to one whole pass (32 chunks), and then `value` is whole-stream prefill tokens/s per layer
+at 131072 tokens.  For any other K the line says which tokens were timed (`config.tokens`,
+`config.chunks_timed`) and carries figures that do not depend on K: `whole_stream` (one complete pass,
+timed on its own) and `steady_state` (steps with the cache at its budget).  Inputs are generated on
+the host from the seeded recipe and are resident in HBM before the clock starts.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,10 +26,24 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 PEAK_F32_TFLOPS = 157.3
 
-# HBM bytes of one steady-state attention launch, from the two rocprofv3 counter runs summarised in
-# profiles/chunk_step_cfg3_llama_128k_hbm_traffic.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-# factors the calibration pass gave).  Only valid for the workload it was measured on.
-MEASURED_ATTENTION_TRAFFIC_BYTES = {"cfg3_llama_128k": 249.6e6}
+
+
+def measured_attention_traffic(workload_name):
+    """(HBM bytes of one steady-state attention launch, source) from the committed rocprofv3 counter summary
+    of this workload (profiles/chunk_step_<workload>_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE, scaled by what
+    the same counters read for a plain copy), or (None, None) when no summary covers the workload.  It is a
+    figure measured in those profiling runs, not in this run."""
+    rel = os.path.join("profiles", f"chunk_step_{workload_name}_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        if line.startswith("locret::attn_") and "merge" not in line:
+            try:
+                return float(line.split()[-1]) * 1e6, rel + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate runs)"
+            except ValueError:
+                return None, None
+    return None, None
 
 
 def attention_flops(w, n_c, T):
@@ -79,12 +96,15 @@ def main():
     w = synth.WORKLOADS[args.workload]
     n_chunks = w.n_chunks
     K = args.steps if args.steps is not None else n_chunks
+    if K < 1:
+        print("bench.py: --steps must be at least 1", file=sys.stderr)
+        sys.exit(2)
     W = args.warmup
     dev = torch.device("cuda:0")
     td = torch.bfloat16 if w.dtype == "bf16" else torch.float32
 
     # ---- inputs: generated per chunk on host threads, uploaded, resident before timing ------------------
-    need = min(n_chunks, max(K, W))
+    need = n_chunks                      # the whole stream: the K-independent figures need every chunk
     t_gen = time.time()
     with ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0)))) as ex:
         host_chunks = list(ex.map(lambda c: synth.chunk(w, c), range(need)))
@@ -144,26 +164,76 @@ def main():
     attn_ms, n_attn = B.locret_profile_read(layer.ctx)
     B.locret_profile_enable(layer.ctx, 0)
 
+    # ---- figures that do not depend on K ------------------------------------------------------------------
+    # (a) one complete pass over the stream from an empty cache, timed on its own the same way
+    plan_full = []
+    n_c = 0
+    for c in range(n_chunks):
+        T = chunks[c][0].shape[0]
+        plan_full.append((n_c, T))
+        n_c = min(n_c + T, w.b)
+    B.locret_profile_enable(layer.ctx, n_chunks)
+    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    f0.record()
+    for c in range(n_chunks):
+        step(c)
+    f1.record()
+    torch.cuda.synchronize()
+    full_ms = f0.elapsed_time(f1)
+    full_attn_ms, n_full = B.locret_profile_read(layer.ctx)
+    # (b) steady state: the cache is at its budget after that pass; the stream's last full chunk again and again
+    c_steady = max(c for c in range(n_chunks) if chunks[c][0].shape[0] == w.B)
+    qs, ks, vs = chunks[c_steady]
+    n_steady = 20
+    steady_possible = B.locret_cache_len(layer.ctx) == w.b
+    for _ in range(2):
+        B.locret_prefill_chunk(layer.ctx, qs, ks, vs, w.B, w.n_s, 1, None, out, scores, None)
+    B.locret_profile_enable(layer.ctx, n_steady)
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s0.record()
+    for _ in range(n_steady):
+        B.locret_prefill_chunk(layer.ctx, qs, ks, vs, w.B, w.n_s, 1, None, out, scores, None)
+    s1.record()
+    torch.cuda.synchronize()
+    steady_ms = s0.elapsed_time(s1) / n_steady
+    steady_attn_ms, n_st = B.locret_profile_read(layer.ctx)
+    B.locret_profile_enable(layer.ctx, 0)
+
     # ---- second pass over the same steps, every stage timed (not part of `value`) ------------------------
-    # In the timed region the selection rides in the first workgroups of the attention launch; here it is
-    # launched on its own (LOCRET_FUSE_SELECT=0, read by the library on every call) so that it has a
-    # duration of its own: the stage figures below are those of the separate kernels.
-    B.locret_profile_mode(layer.ctx, 0)
+    # In the timed region the selection rides in the first workgroups of the attention launch; here a second
+    # context, created with LOCRET_FUSE_SELECT=0 (the library reads its launch switches when a context is
+    # created), launches it on its own so that it has a duration of its own: the stage figures below are
+    # those of the separate kernels.
     fuse_before = os.environ.get("LOCRET_FUSE_SELECT")
     os.environ["LOCRET_FUSE_SELECT"] = "0"
-    for i in range(min(K, 6)):           # untimed: the selection kernels are loaded on their first launch
-        step(i)
-    torch.cuda.synchronize()
-    B.locret_profile_enable(layer.ctx, K)
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
+    layer_st = B.LocretLayer(B.config_from_workload(w), dev)
     if fuse_before is None:
         del os.environ["LOCRET_FUSE_SELECT"]
     else:
         os.environ["LOCRET_FUSE_SELECT"] = fuse_before
-    stage_ms, n_prof = B.locret_profile_read(layer.ctx)
-    B.locret_profile_enable(layer.ctx, 0)
+    layer_st.set_weights(torch.from_numpy(W1h).to(dev).to(td), torch.from_numpy(W2h).to(dev).to(td))
+
+    def step_st(i):
+        c = i % need
+        if c == 0:
+            B.locret_reset(layer_st.ctx)
+        q, k, v = chunks[c]
+        B.locret_prefill_chunk(layer_st.ctx, q, k, v, q.shape[0], w.n_s, 1, None, out, scores, None)
+
+    B.locret_profile_mode(layer_st.ctx, 0)
+    for i in range(min(K, 6)):           # untimed: the selection kernels are loaded on their first launch
+        step_st(i)
+    torch.cuda.synchronize()
+    B.locret_profile_enable(layer_st.ctx, K)
+    for i in range(K):
+        step_st(i)
+    torch.cuda.synchronize()
+    stage_ms, n_prof = B.locret_profile_read(layer_st.ctx)
+    B.locret_profile_enable(layer_st.ctx, 0)
+    layer_st.close()
+    del layer_st
     stage_ms = list(stage_ms)
     if n_attn == K:                      # the live figure of the timed region (else: a kernel that is timed with events)
         stage_ms[1] = attn_ms[1]
@@ -174,10 +244,18 @@ def main():
     ms = dict(zip(B.PROF_STAGE_NAMES, stage_ms))
     peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
     attn_tflops = fl_attn / (ms["attention"] * 1e-3) / 1e12
+    traffic, traffic_source = measured_attention_traffic(w.name)
+    if args.traffic_bytes is not None:
+        traffic, traffic_source = args.traffic_bytes, "--traffic-bytes"
+    steady_attn_tflops = (attention_flops(w, w.b, w.B) * n_steady / (steady_attn_ms[1] * 1e-3) / 1e12
+                          if (n_st == n_steady and steady_possible) else None)
     roofline = {
         "kernel": "attention", "bound": "mfma", "achieved": round(attn_tflops, 2), "peak": peak, "unit": "TFLOP/s",
         "frac": round(attn_tflops / peak, 4),
-        "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_ATTENTION_TRAFFIC_BYTES.get(w.name),
+        "steady_achieved": round(steady_attn_tflops, 2) if steady_attn_tflops else None,
+        "steady_frac": round(steady_attn_tflops / peak, 4) if steady_attn_tflops else None,
+        "steady_launch_ms": round(steady_attn_ms[1] / n_steady, 4) if steady_attn_tflops else None,
+        "traffic": traffic, "traffic_source": traffic_source,
         "algorithmic_bytes_steady": (2 * w.h_kv * (w.b + w.B) + 2 * w.B * w.h) * w.d * (2 if w.dtype == "bf16" else 4),
         "avg_launch_ms": round(ms["attention"] / max(1, n_prof), 4),
         "timed_by": "kernel dispatch timestamps, inside the timed region" if n_attn == K else "events around the launch, second pass",
@@ -204,6 +282,12 @@ def main():
                            "note": "both as kernels of their own (second pass); in the timed region the selection runs "
                                    "inside the attention launch" if sel_fused else "both as kernels of their own"},
         "input_gen_s": round(t_gen, 1),
+        "whole_stream": {"tokens": w.N, "steps": n_chunks, "ms": round(full_ms, 3),
+                         "tokens_per_s": round(w.N / (full_ms * 1e-3), 1),
+                         "attention_frac": (round(sum(attention_flops(w, nc, T) for nc, T in plan_full)
+                                                  / (full_attn_ms[1] * 1e-3) / 1e12 / peak, 4) if n_full == n_chunks else None)},
+        "steady_state": ({"n_c": w.b, "T": w.B, "steps": n_steady, "ms_per_step": round(steady_ms, 4),
+                          "tokens_per_s": round(w.B / (steady_ms * 1e-3), 1)} if steady_possible else None),
     }
 
     # ---- decode step (Eq. 1 with B = 1): one generated token over the full budget ----------
@@ -268,7 +352,10 @@ def main():
         "metric": "prefill tokens/sec per layer at 128K ctx", "value": round(tokens / (total_ms * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(total_ms / K, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "tokens": w.N, "chunk": w.B, "budget": w.b, "stabilizers": w.n_s,
+        "config": {"workload": w.name, "tokens": tokens, "stream_tokens": w.N,
+                   "chunks_timed": (f"{K // n_chunks} whole pass(es) of {n_chunks} chunks" if K % n_chunks == 0 else
+                                    f"{K // n_chunks} whole pass(es) + chunks 0-{K % n_chunks - 1} of {n_chunks}, each pass from an empty cache"),
+                   "chunk": w.B, "budget": w.b, "stabilizers": w.n_s,
                    "heads": f"{w.h}q/{w.h_kv}kv x{w.d}", "d_R": w.d_R},
         "roofline": roofline, "cpu_baseline": cpu, **extra,
     }
@@ -309,7 +396,18 @@ def cpu_baseline(w, host_chunks, rows_per_head):
     o.evict_compact(sc, k, v, w.n_s)
     t_rest = time.time() - t3
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    # the small configuration (config 1: float32 inputs, 4096 tokens as 8 chunks of 512) through the oracle in full
+    w1 = synth.WORKLOADS["cfg1_f32_gqa_4k"]
+    W1a, W2a = synth.weights(w1)
+    o1 = LocretLayerOracle(w1.h, w1.h_kv, w1.d, w1.b, W1a, W2a, w1.rh_kv_expand, w1.rope, w1.theta)
+    c1 = [synth.chunk(w1, c) for c in range(w1.n_chunks)]
+    t4 = time.time()
+    for q1, k1, v1 in c1:
+        o1.prefill_chunk(q1, k1, v1, w1.n_s)
+    t_cfg1 = time.time() - t4
     return {
+        "config1_full_stream": {"workload": w1.name, "tokens": w1.N, "seconds": round(t_cfg1, 3),
+                                "tokens_per_s": round(w1.N / t_cfg1, 1)},
         "value": round(T / (t_attn_full + t_rest), 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": f"one steady-state chunk (n_c={w.b}, T={T}): retaining head + select + compact in full "
                   f"({t_rest:.2f}s); attention on {len(r1)} and {len(r2)} query rows x {w.h} heads "

@@ -20,8 +20,8 @@ Readings taken where the paper leaves a choice (each is restated where used):
   * The retaining head sees q, k, v before any rotary embedding, so that a score,
     once computed, does not depend on the position a unit later occupies (Section 3.4).
   * K is cached un-rotated; at every step cache slot i takes position i and chunk
-    token t takes position n_c + t (Section 3.4, "reassign continuous position
-    embeddings from the beginning"); rotate-half pairing (i, i + d/2),
+    token t takes position n_c + t (Section 3.4: positions are handed out anew,
+    contiguously from zero, at every step); rotate-half pairing (i, i + d/2),
     inverse frequency theta^(-2i/d).
   * The +infinity written on the stabilizers is a selection-time mask: the cache
     keeps each unit's true score.

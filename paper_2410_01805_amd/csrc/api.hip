@@ -44,7 +44,27 @@ int validate(const locret_config* c) {
   return LOCRET_OK;
 }
 
+int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return (e && *e) ? atoi(e) : dflt;
+}
+
+// The launch switches (tests, measurements): the only place the environment is read, once per context.
+Tuning tuning_from_env() {
+  Tuning t;
+  const char* v = getenv("LOCRET_ATTN_VARIANT");
+  t.attn_regstaged = v && !strcmp(v, "regstaged");
+  t.pp_split = env_int("LOCRET_PP_SPLIT", -1);
+  t.pp_spread = env_int("LOCRET_PP_SPREAD", -1);
+  t.score_split = env_int("LOCRET_SCORE_SPLIT", -1);
+  const int dk = env_int("LOCRET_DEC_KEYS", 0);
+  t.dec_keys = (dk >= 64 && dk <= 65536 && dk % 64 == 0) ? dk : 0;
+  t.fuse_select = env_int("LOCRET_FUSE_SELECT", 1) != 0;
+  return t;
+}
+
 void fill_dims(const locret_config* c, Dims* D) {
+  D->tune = tuning_from_env();
   D->h = c->n_q_heads;
   D->h_kv = c->n_kv_heads;
   D->g = D->h / D->h_kv;
@@ -423,12 +443,10 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   bool ok = true;
   // The selection depends on the scores only.  Where the attention launch can carry it (direct-to-LDS kernel, head_dim 128 or 96,
   // few enough candidates for its register-resident form) the retaining head runs first and the selection
-  // rides in the first workgroups of the attention launch; LOCRET_FUSE_SELECT=0 (read per call) keeps the
-  // separate launch.
-  const char* fs = getenv("LOCRET_FUSE_SELECT");
+  // rides in the first workgroups of the attention launch (Tuning::fuse_select = 0 keeps the separate launch).
   bool fuse_select = false;
   SelectArgs sa{};
-  if (evict && !c->overlap && c->mfma_attn && !(fs && fs[0] == '0')) {
+  if (evict && !c->overlap && c->mfma_attn) {
     sa = select_args(c, L, n_stab, kept_idx_out);
     fuse_select = attention_bf16_fuses_select(D, sa.L - sa.n_stab - sa.n_pin);
   }

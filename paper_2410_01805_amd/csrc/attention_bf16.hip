@@ -18,7 +18,7 @@
 // exchange with lane^32, and P^T leaves the accumulator already in B-operand order provided the
 // V^T tile stores its keys in the matching order (each group of 16 keys as 0-3, 8-11, 4-7, 12-15).
 //
-// Softmax as in attention_dma.hip: queries pre-scaled by scale * log2(e) (and rotated here when the
+// Softmax as in attention_pp.hip: queries pre-scaled by scale * log2(e) (and rotated here when the
 // rotary table is passed), S chains started from -(running max), exp2 / bf16 pack / two-way dot
 // products per tile, the running max moved only on the first tile and when a lane's probability
 // sum reaches 2^8.
@@ -409,8 +409,7 @@ static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const flo
   const int n_hgroups = Dm.h / hpw;
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
-  const char* sp_e = getenv("LOCRET_PP_SPREAD");
-  const int spread = hl.ragged && !(sp_e && sp_e[0] == '0');
+  const int spread = hl.ragged && Dm.tune.pp_spread != 0;
   const int n_wg = spread ? n_hgroups * ((n_ttiles + 7) / 8) * 8 : n_hgroups * n_ttiles;
   hipExtLaunchKernelGGL((attn_mfma_kernel<D, QB, NW, WPE>), dim3(n_wg), dim3(NW * 64), 0, st, tm.start, tm.stop,
                         0, (const bf16_t*)q, tab,
@@ -418,54 +417,31 @@ static void attn_launch(const Dims& Dm, LaunchTimer tm, const void* q, const flo
                      n_hgroups, n_ttiles, hl, spread, longest_first(hl, Dm.h_kv));
 }
 
-// LOCRET_ATTN_VARIANT selects a kernel for experiments: default "pp" (direct-to-LDS staging with the two
-// wavefronts of a SIMD in anti-phase, attention_pp.hip; head_dim 128 only, other head dims fall through
-// to "w8"); "dma" the same staging with free-running wavefronts (attention_dma.hip), "dma4" its
-// 4-wavefront form; "w8" register-staged, 8 wavefronts per workgroup; "w4" 4 wavefronts, two
-// workgroups per CU; "qb2" 4 wavefronts with 64 queries each; "pipe" attention_pipe.hip.
-static int attn_variant() {      // read on every launch (cheap), so a process can compare variants
-  const char* e = getenv("LOCRET_ATTN_VARIANT");
-  int v = 6;
-  if (e && !strcmp(e, "w8")) v = 0;
-  if (e && !strcmp(e, "dma")) v = 4;
-  if (e && !strcmp(e, "dma4")) v = 5;
-  if (e && !strcmp(e, "w4")) v = 1;
-  if (e && !strcmp(e, "qb2")) v = 2;
-  if (e && !strcmp(e, "pipe")) v = 3;
-  return v;
+// The direct-to-LDS kernel (attention_pp.hip) serves head dims 128 and 96 while byte offsets inside one head's
+// cache fit 31 bits; everything else, and every shape when the context's switches ask for it, runs on the
+// register-staged kernel above.
+static bool pp_applies(const Dims& Dm) {
+  return !Dm.tune.attn_regstaged && (Dm.d == 128 || Dm.d == 96) && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
 }
 
-static bool dma_applies(const Dims& Dm) {      // a direct-to-LDS kernel serves this shape: "pp" head dims 128 and 96, "dma" 128
-  const int v = attn_variant();
-  return v >= 4 && (Dm.d == 128 || (v == 6 && Dm.d == 96)) && (int64_t)Dm.cap * Dm.d * 2 < (1ll << 31);
-}
+// true when launch_attention_bf16 hands its LaunchTimer to the kernel's own dispatch
+bool attention_bf16_attaches_timer(const Dims& Dm) { return Dm.d == 64 || Dm.d == 96 || Dm.d == 128; }
 
-// true when launch_attention_bf16 hands its LaunchTimer to the kernel's own dispatch (every kernel here
-// except the half-tile pipeline, which ignores it)
-bool attention_bf16_attaches_timer(const Dims& Dm) {
-  return (attn_variant() != 3 || dma_applies(Dm)) && (Dm.d == 64 || Dm.d == 96 || Dm.d == 128);
-}
-
-// every kernel here except the half-tile pipeline takes un-rotated queries and rotates them itself
-bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope && (attn_variant() != 3 || dma_applies(Dm)); }
+// the matrix-core kernels take un-rotated queries and rotate them themselves
+bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope; }
 
 bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
-  return Dm.bf16 && attn_variant() == 6 && dma_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
+  return Dm.bf16 && Dm.tune.fuse_select && pp_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
 }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel,
                            const HeadLens* n_c_h, float* split_part, size_t split_floats) {
-  const int v = attn_variant();
   const HeadLens hl = head_lens_or_common(n_c_h);
-  if (v == 6 && dma_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h, split_part, split_floats)) return;
-  if (dma_applies(Dm) && launch_attention_bf16_dma(Dm, v - 4, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
-  if (v == 3 && launch_attention_bf16_pipe(Dm, q, Kx, V, out, T, n_c, scale, st, n_c_h)) return;
-#define LOCRET_CASE(DD)                                                                           \
-  case DD:                                                                                        \
-    if (v == 1) attn_launch<DD, 1, 4, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl);    \
-    else if (v == 2) attn_launch<DD, 2, 4, 1>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl); \
-    else attn_launch<DD, 1, 8, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl);           \
+  if (pp_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h, split_part, split_floats)) return;
+#define LOCRET_CASE(DD)                                                                        \
+  case DD:                                                                                     \
+    attn_launch<DD, 1, 8, 2>(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, hl);           \
     break;
   switch (Dm.d) {
     LOCRET_CASE(64)

@@ -1,5 +1,17 @@
-// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950, head_dim 128 (and 96): the direct-to-LDS kernel
-// of attention_dma.hip with its two wavefronts per SIMD held in anti-phase.
+// Chunk attention (Eq. 1) on the bf16 matrix cores of gfx950, head_dim 128 (and 96): K and V tiles go
+// global -> LDS directly (buffer_load ... lds), and the two wavefronts of every SIMD are held in anti-phase.
+//
+// Products are formed transposed with v_mfma_f32_32x32x16_bf16: S^T = K Q^T (A = 32 key rows from LDS, B = the
+// wavefront's 32 queries, held in registers for the whole kernel, pre-scaled by scale * log2 e and rotated),
+// O^T += V^T P^T (A = V^T from LDS through the transposing read ds_read_b64_tr_b16, B = P^T straight from the S
+// accumulator registers: a lane holds 16 keys of ONE query there, so row sums are per-lane scalars and P needs
+// no shuffle).  A tile is 64 keys x 128 dims of K and of V, rows of 256 bytes.  A direct load writes lane L's
+// 16 bytes at base + 16 L, so rows cannot be padded; bank conflicts are avoided by choosing WHICH 16-byte
+// chunk a lane fetches: position c' of K row r holds chunk c' ^ (r & 15), of V row r chunk c' ^ ((r & 3) << 2).
+// Tiles past the end are fetched through a zero-length buffer descriptor (they arrive as zeros).
+// Softmax: every S chain starts from an accumulator holding -(running max), so the MFMA result is the exponent;
+// the running max is set by the first tile and raised only when a lane's probability sum over its 32 keys
+// reaches 2^8 (which also catches any overflow).
 //
 // A wavefront's tile is a chain S (16 MFMAs) -> softmax (32 exp2 on the transcendental unit, ~640
 // cycles) -> PV (16 MFMAs).  Left alone, the two wavefronts of a SIMD drift into the same phase:
@@ -30,8 +42,6 @@
 // cannot tell that those reads never touch a stage with a load in flight), which would stall every
 // PV block on the loads just issued.  LDS operations return in order, so a count of the asm reads
 // issued after the wanted one is always sufficient, whatever else the compiler has in flight.
-//
-// Tile layout in LDS, swizzles, fragment addressing and the softmax are those of attention_dma.hip.
 #include <hip/hip_ext.h>
 
 #include "attn_common.h"
@@ -324,14 +334,18 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
         ps = ps0 + ps1;
       };
       exp_pack_sum();
-      if (fresh || __any(!(ps < 256.f))) {     // rare: move the running max (see attention_dma.hip)
+      if (fresh || __any(!(ps < 256.f))) {     // rare: set or raise the running max
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
         mx = max_across_halves(mx);
-        const float delta = fresh ? mx : fmaxf(mx, 0.f);
+        // Key-split launches only: in the split that holds the diagonal a query may see none of the split's keys
+        // (its row of the first tile is wholly masked, and every later tile lies further right).  Such a lane keeps
+        // max 0 and sum 0, and the merge kernel drops partials whose sum is 0; without the test it would form
+        // -inf - (-inf).  In unsplit launches every query sees key 0, which lies in the first tile.
+        const float delta = fresh ? ((GENERAL && mx == -INFINITY) ? 0.f : mx) : fmaxf(mx, 0.f);
         const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-delta);
         m_run += delta;
         l_run *= alpha;
@@ -527,18 +541,16 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
   const int n_ttiles = (T + TW - 1) / TW;
   const float c_log2 = scale * 1.4426950408889634f;
   const int n_sel = sel ? Dm.h_kv : 0;
-  const char* sp_e = getenv("LOCRET_PP_SPREAD");
   const HeadLens hl = head_lens_or_common(n_c_h);
   const SelectArgs sa = sel ? *sel : SelectArgs{};
   // Key split: a short chunk has too few (head group, token tile) items for the 256 CUs (chunks of 1024 tokens of
   // a 32-head layer: 128), so each item is cut into n_split key ranges, as many as bring the launch to about one
   // workgroup per CU, and a second kernel merges the partial results.  Only while every split still has a
-  // few key tiles in every head and the partials fit their buffer.  LOCRET_PP_SPLIT (read per launch): 0 = never,
+  // few key tiles in every head and the partials fit their buffer.  Tuning::pp_split: 0 = never,
   // k = always k ranges (bounded by the buffer only).
   int n_split = 1;
   if (split_part != nullptr) {
-    const char* se = getenv("LOCRET_PP_SPLIT");
-    const int forced = se ? atoi(se) : -1;
+    const int forced = Dm.tune.pp_split;
     int min_nc = n_c;
     if (hl.ragged) for (int m = 0; m < Dm.h_kv; ++m) min_nc = hl.v[m] < min_nc ? hl.v[m] : min_nc;
     const int items = n_hgroups * n_ttiles;
@@ -549,7 +561,7 @@ bool launch_attention_bf16_pp(const Dims& Dm, LaunchTimer tm, const void* q, con
     n_split = want < 1 ? 1 : want;
   }
   const int n_tt_eff = n_ttiles * n_split;
-  const int spread = (hl.ragged && !(sp_e && sp_e[0] == '0')) || (sp_e && sp_e[0] == '1');
+  const int spread = (hl.ragged && Dm.tune.pp_spread != 0) || Dm.tune.pp_spread == 1;
   const int n_wg = spread ? n_hgroups * ((n_tt_eff + 7) / 8) * 8 : n_hgroups * n_tt_eff;
   float* part = n_split > 1 ? split_part : nullptr;
 #define LOCRET_PP_LAUNCH(SP)                                                                                          \

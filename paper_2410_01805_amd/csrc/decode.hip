@@ -338,23 +338,13 @@ __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const f
   }
 }
 
-// Keys per split.  LOCRET_DEC_KEYS (read once; a multiple of 64 in 64 .. 65536) fixes it; otherwise it is chosen per
+// Keys per split.  Tuning::dec_keys (a multiple of 64 in 64 .. 65536) fixes it; otherwise it is chosen per
 // launch so that the launch has about 700 workgroups (2.7 per CU), but never under 128 keys, in steps of 64.
 // Measured per token, end to end: 8 heads x 16.6K units 24.0 us at 192 keys (25.4 at 256), 32 heads x 8.4K units
 // 21.5 us at 384 (22.6 at 256), 8 heads x 6.4K units 14.7 us at 128 (18.6 at 64, 15.6 at 256).
 constexpr int DEC_KEYS_MIN = 128;
-static int decode_keys_env() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("LOCRET_DEC_KEYS");
-    const int x = e ? atoi(e) : 0;
-    v = (x >= 64 && x <= 65536 && x % 64 == 0) ? x : 0;
-  }
-  return v;
-}
-
 int decode_keys_per_split(const Dims& D, int n_keys) {
-  if (decode_keys_env() > 0) return decode_keys_env();
+  if (D.tune.dec_keys > 0) return D.tune.dec_keys;
   const int64_t want = ((int64_t)D.h_kv * n_keys + 703) / 704;
   int k = (int)((want + 63) / 64 * 64);
   if (k < DEC_KEYS_MIN) k = DEC_KEYS_MIN;
@@ -364,7 +354,7 @@ int decode_keys_per_split(const Dims& D, int n_keys) {
 
 // partials per query head at most: the splits over a full cache at the smallest split size, and the new token's
 int decode_max_splits(const Dims& D) {
-  const int kmin = decode_keys_env() > 0 ? decode_keys_env() : DEC_KEYS_MIN;
+  const int kmin = D.tune.dec_keys > 0 ? D.tune.dec_keys : DEC_KEYS_MIN;
   return (D.cap + kmin - 1) / kmin + 1;
 }
 

@@ -47,7 +47,7 @@ inline HeadOrder longest_first(const HeadLens& hl, int h_kv) {
   return o;
 }
 
-// One selection (Section 3.3, Eq. 4 with the stabilizer mask of Section 3.4) for every KV head: scores S[m][cap],
+// One selection (Section 3.4 and Algorithm 1: stabilizer mask, then top-b) for every KV head: scores S[m][cap],
 // units [0, L), n_keep kept per head = the first n_pin units, the best of the middle ones, the last n_stab.
 struct SelectArgs {
   const float* S;
@@ -69,7 +69,20 @@ struct SelectArgs {
   HeadLens L_h, keep_h;
 };
 
+// Launch switches for tests and measurements.  Read from the environment when a context is sized and created
+// (LOCRET_ATTN_VARIANT, LOCRET_PP_SPLIT, LOCRET_PP_SPREAD, LOCRET_SCORE_SPLIT, LOCRET_DEC_KEYS,
+// LOCRET_FUSE_SELECT), and carried with the context's dimensions; no launch path reads the environment.
+struct Tuning {
+  int attn_regstaged = 0;   // 1: the register-staged attention kernel also where the direct-to-LDS one applies
+  int pp_split = -1;        // key ranges per item of the direct-to-LDS attention kernel: -1 chosen per launch, 0 never, k always k
+  int pp_spread = -1;       // its workgroup order: -1 by head lengths, 0 one KV head per XCD, 1 every head over all XCDs
+  int score_split = -1;     // contraction slices of the retaining head: -1 chosen per launch, 0 never, k always k
+  int dec_keys = 0;         // keys per split of the decode step: 0 chosen per launch, else a multiple of 64 in 64..65536
+  int fuse_select = 1;      // 0: the selection is always a launch of its own
+};
+
 struct Dims {
+  Tuning tune;
   int h;        // query heads
   int h_kv;     // KV heads
   int g;        // h / h_kv
@@ -110,14 +123,8 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
 // n_c_h (every attention launcher): per-head cache lengths, or NULL when all heads hold n_c units.
 void launch_attention_simple(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
                              int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
-// Software-pipelined bf16 MFMA kernel (d in {64, 96, 128}); false if the shape is not covered.
-bool launch_attention_bf16_pipe(const Dims& D, const void* q, const void* Kx, const void* V, void* out,
-                                int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
-// bf16 MFMA kernel with K/V staged global->LDS directly (d = 128 only); false if the shape is not
-// covered.  variant 0: 8 wavefronts and a 4-tile ring; 1: 4 wavefronts and a 2-tile ring.
-bool launch_attention_bf16_dma(const Dims& D, int variant, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                               int T, int n_c, float scale, hipStream_t st, const HeadLens* n_c_h = nullptr);
-// The same kernel with the two wavefronts of every SIMD held one S block apart (attention_pp.hip).
+// bf16 MFMA kernel with K/V staged global -> LDS directly and the two wavefronts of every SIMD held one S block
+// apart (attention_pp.hip; d = 128 or 96); false if the shape is not covered.
 bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx,
                               const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
                               const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr,

@@ -360,7 +360,7 @@ int score_parts_bf16(const Dims& D) {
 
 // Returns the number of partial score tensors written to `part` (the caller sums them): d_R / 128, or 1 when the
 // launch split the contraction (short chunks: at most a quarter as many 128 x 128 tiles as CUs; each slice keeps
-// at least 8 stages; LOCRET_SCORE_SPLIT, read per launch: 0 = never, k = k slices).  Measured on 32q/8kv x 128,
+// at least 8 stages; Tuning::score_split: 0 = never, k = k slices).  Measured on 32q/8kv x 128,
 // d_R = 1024: chunks of 1024 tokens (64 tiles, 4 slices) 49 -> 37 us; chunks of 2048 (128 tiles, 2 slices) gained
 // nothing in the head and cost attention 8 % (16 MB of partials through the L2), so two slices are not taken.
 int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T, const void* W1t,
@@ -368,8 +368,7 @@ int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v
   dim3 grid((T + RT_N - 1) / RT_N, D.d_R / RT_M);
   int n_z = 1;
   if (zpart != nullptr) {
-    const char* e = getenv("LOCRET_SCORE_SPLIT");
-    const int forced = e ? atoi(e) : -1;
+    const int forced = D.tune.score_split;
     const int tiles = (int)(grid.x * grid.y), stages = D.K / RT_K;
     n_z = forced >= 0 ? forced : (256 / tiles >= 4 ? 256 / tiles : 1);
     n_z = n_z > 8 ? 8 : n_z;

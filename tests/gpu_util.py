@@ -43,11 +43,22 @@ def host(t: torch.Tensor) -> np.ndarray:
 # belongs to: an attention output row is one convex combination of value rows, so its error
 # scales with that row's magnitude (rows that see few keys are O(1), rows that average thousands
 # are O(0.01)); scores are compared against the scale of the whole tensor.
-# The tensor-wide bar max|d| <= 2e-2 max|ref| always applies.  The element-wise bar is widened by
-# `kappa` = the factor by which a workload scales some key norms (config 3 plants keys 4x): a logit
-# is c * sum q_i k_i with each factor rounded to bf16 after rotation, so its absolute error is about
-# 2^-8.5 |q||k| / sqrt(d) ~ 3e-3 * key scale, and that is the relative error of the probabilities of
-# exactly the keys that dominate such a row.
+# The tensor-wide bar max|d| <= 2e-2 max|ref| always applies.  The element-wise bar is
+# |d| <= kappa (2e-2 |ref| + 2e-2 rms) with kappa = 1, except on the workload whose keys are planted 4x
+# larger (config 3), where the roundings that bf16 matrix-core arithmetic forces on ANY kernel (rotated q
+# and k as bf16 operands) alone reach 4.13 x the kappa = 1 bound over a whole steady-state chunk:
+# tests/test_bf16_floor.py measures that floor on the CPU and checks that KAPPA_PLANTED_X4 is it plus a
+# margin of 1.2-1.5.  The full-size GPU test also holds the kernel to kappa = 1 against the forced-rounding
+# model itself, which is the check of the kernel's own error.
+KAPPA_PLANTED_X4 = 5.25
+
+WORST = {}      # what -> largest |d| / bound seen by assert_close in this process (headroom; printed by the tests)
+
+
+def kappa_for(w) -> float:
+    return KAPPA_PLANTED_X4 if w.planted_scale > 1.0 else 1.0
+
+
 def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", per_row: bool = False,
                  kappa: float = 1.0):
     got = got.astype(np.float64)
@@ -60,21 +71,36 @@ def assert_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", p
         scale = np.abs(ref).max()
         assert diff.max() <= 2e-2 * scale, f"{what}: max |d|={diff.max():.3e} vs 2e-2*{scale:.3e}"
         rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True)) if per_row else np.sqrt(np.mean(ref ** 2))
-        bound = max(1.0, kappa) * (2e-2 * np.abs(ref) + 2e-2 * rms)
+        bound = kappa * (2e-2 * np.abs(ref) + 2e-2 * rms)
+    ratio = float((diff / np.maximum(bound, 1e-300)).max()) if diff.size else 0.0
+    WORST[what] = max(WORST.get(what, 0.0), ratio)
+    print(f"[parity] {what}: worst |d|/bound = {ratio:.3f} (kappa {kappa:g}, {diff.size} elements)")
     bad = diff > bound
     if bad.any():
         i = np.unravel_index(np.argmax(diff - bound), diff.shape)
         raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements out of tolerance ({dtype}); worst at {i}: "
                              f"got {got[i]:.6g} ref {ref[i]:.6g} bound {np.broadcast_to(bound, diff.shape)[i]:.3g}")
+    return ratio
 
 
-def near_threshold_ok(scores_cat: np.ndarray, kept_gpu, kept_ref, tol_rel: float) -> bool:
-    """Free-running protocol: units in the symmetric difference must sit within tol of the
-    selection threshold (the smallest kept candidate score)."""
+def near_threshold_ok(scores_cat: np.ndarray, kept_gpu, kept_ref, tol_rel: float, n_stab: int = 0, n_pin: int = 0) -> bool:
+    """Free-running protocol: the two kept sets may differ only in CANDIDATES (units that are neither among the
+    last n_stab nor in the pinned prefix) whose score lies within tol_rel * max|score| of the selection threshold
+    = the smallest score among the candidates the reference kept."""
+    L = len(scores_cat)
+    ns = min(n_stab, L)
+    npin = min(n_pin, L - ns)
+    lo, hi = npin, L - ns                                  # candidates are [lo, hi)
     a, b = set(kept_gpu.tolist()), set(kept_ref.tolist())
     sym = sorted(a ^ b)
     if not sym:
         return True
-    thr = min(scores_cat[i] for i in (a & b)) if (a & b) else 0.0
-    lim = tol_rel * max(1e-30, float(np.abs(scores_cat).max()))
+    if any(i < lo or i >= hi for i in sym):
+        return False                                       # a stabilizer or a pinned unit was dropped
+    kept_cand = [i for i in b if lo <= i < hi]
+    if not kept_cand:
+        return False
+    thr = min(float(scores_cat[i]) for i in kept_cand)
+    finite = np.abs(scores_cat[np.isfinite(scores_cat)])
+    lim = tol_rel * max(1e-30, float(finite.max()) if finite.size else 0.0)
     return all(abs(float(scores_cat[i]) - thr) <= lim for i in sym)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2410_01805_amd import synth
-from tests.gpu_util import DEV, assert_close, dev, host, make_layer, make_oracle
+from tests.gpu_util import DEV, assert_close, dev, host, kappa_for, make_layer, make_oracle
 from tests.test_gpu_prefill import _run_stream
 
 pytestmark = pytest.mark.gpu
@@ -123,5 +123,5 @@ def test_decode_on_the_full_budget_of_config3():
         q, k, v = synth.tokens(w, 5 * w.B + i, 5 * w.B + i + 1)
         out_ref, _, _ = o.prefill_chunk(q, k, v, 0, evict=False)
         out, _ = layer.decode_step(dev(q, w), dev(k, w), dev(v, w), with_score=False)
-        assert_close(host(out), out_ref, w.dtype, f"cfg3 decode token {i}", per_row=True, kappa=w.planted_scale)
+        assert_close(host(out), out_ref, w.dtype, f"cfg3 decode token {i}", per_row=True, kappa=kappa_for(w))
     layer.close()

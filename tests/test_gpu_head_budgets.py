@@ -148,9 +148,8 @@ def test_chunk_step_with_head_budgets_and_pinned_prefix():
     layer.close()
 
 
-@pytest.mark.parametrize("variant", ["dma", "dma4", "w8", "w4", "qb2", "pipe"])
-def test_alternative_attention_kernels_with_head_budgets(variant, monkeypatch):
-    monkeypatch.setenv("LOCRET_ATTN_VARIANT", variant)
+def test_register_staged_attention_kernel_with_head_budgets(monkeypatch):
+    monkeypatch.setenv("LOCRET_ATTN_VARIANT", "regstaged")
     w = synth.tiny(**STREAMS[2][0])
     layer, o = _run_stream(w, STREAMS[2][1])
     layer.close()
@@ -169,7 +168,7 @@ def test_other_launch_orders_with_head_budgets(env, monkeypatch):
 
 # The matrix-core attention kernels deal their workgroups differently when the heads differ in length: every XCD
 # takes every eighth token tile of every head, longest head first, instead of one head per XCD (8 token tiles here:
-# whole rounds of the 8 XCDs; the other streams of this file have tile counts that leave the last round short).  LOCRET_PP_SPREAD (read per launch) = 0 keeps one head per XCD, 1 forces the other order.
+# whole rounds of the 8 XCDs; the other streams of this file have tile counts that leave the last round short).  LOCRET_PP_SPREAD (read when the context is created) = 0 keeps one head per XCD, 1 forces the other order.
 SPREAD = dict(name="hb_spread", dtype="bf16", h=16, h_kv=4, d=128, N=3584, B=512, b=1100, n_s=64, d_R=128)
 
 
