@@ -35,12 +35,25 @@ Readings taken where the paper leaves a choice (each is restated where used):
     within its own cache (slot i of head m sits at position i, chunk token t at
     n_c[m] + t).
 
+  * Quantized cache rows (Appendix "Orthogonality to Other Methods", combination with 4-bit
+    KV-cache quantization; the paper uses a third-party quantizer and gives no format).
+    Reading: every K and V row is quantized when it enters the cache, per unit and per
+    group of 32 consecutive head dims (a unit must stay self-contained, because units are
+    evicted one by one): asymmetric 4-bit codes, code = round-half-even((x - lo) / s) clamped
+    to 0..15 with lo = the group's minimum and s = (max - min) / 15 rounded to bfloat16
+    (s = 1 for a constant group), decided in float32; value = lo + code * s.  K is quantized
+    un-rotated.  Attention reads the cache, so it sees dequantized rows, the chunk's own
+    included; the retaining head sees the raw q, k, v.
+
 Parity pins (tests/test_oracle_*.py): brute-force dense masked attention written
 with Python loops, a library SDPA for the never-evicting case, sliding-window
 special case, closed-form kept sets, the two cache-problem conditions of
 Appendix "Causal Importance Score Simulates a Cache Problem", a triple-loop MLP,
 the bookkeeping numbers the paper prints (tests/golden/), and for head-wise budgets
-the closed form and the brute force applied head by head.
+the closed form and the brute force applied head by head; for the 4-bit rows hand-worked
+groups with their packed bytes written out, the half-step round-trip bound, nearest-code
+brute force, and the layer with quantized rows == the plain layer fed dequantized k, v
+(tests/test_oracle_quant.py).
 """
 from __future__ import annotations
 
@@ -125,17 +138,79 @@ def select_keep(scores: np.ndarray, budget: int, n_stab: int, n_pin: int = 0) ->
 
 
 # ----------------------------------------------------------------------------
+# 4-bit cache rows (Appendix "Orthogonality to Other Methods", quantization combination)
+# ----------------------------------------------------------------------------
+
+Q4_GROUP = 32       # consecutive head dims that share one (scale, minimum) pair
+
+
+def _bf16_round(x32: np.ndarray) -> np.ndarray:
+    """float32 -> nearest bfloat16 (ties to even), returned as float32."""
+    u = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32)
+    r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) << np.uint32(16)
+    return r.view(np.float32)
+
+
+def quantize_rows_q4(x: np.ndarray):
+    """x [n][d] (values representable in bfloat16, d a multiple of 32) -> (codes uint8 [n][d] in 0..15,
+    scale float32 [n][d/32] holding bfloat16 values, lo float32 [n][d/32]).
+    Every step is float32, the precision in which the code is decided."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n, d = x.shape
+    assert d % Q4_GROUP == 0
+    g = x.reshape(n, d // Q4_GROUP, Q4_GROUP)
+    lo = g.min(axis=2)
+    hi = g.max(axis=2)
+    scale = _bf16_round((hi - lo) / np.float32(15.0))
+    scale = np.where(scale > 0, scale, np.float32(1.0)).astype(np.float32)
+    t = (g - lo[:, :, None]) / scale[:, :, None]                  # float32 subtraction and division
+    codes = np.clip(np.rint(t), 0, 15).astype(np.uint8)          # rint: ties to even
+    return codes.reshape(n, d), scale, lo.astype(np.float32)
+
+
+def dequantize_rows_q4(codes: np.ndarray, scale: np.ndarray, lo: np.ndarray) -> np.ndarray:
+    """value = lo + code * scale, exactly (float64)."""
+    n, d = codes.shape
+    c = codes.reshape(n, d // Q4_GROUP, Q4_GROUP).astype(np.float64)
+    return (lo.astype(np.float64)[:, :, None] + c * scale.astype(np.float64)[:, :, None]).reshape(n, d)
+
+
+def pack_rows_q4(codes: np.ndarray, scale: np.ndarray, lo: np.ndarray) -> np.ndarray:
+    """Storage form of the rows, uint8 [n][d/2 + 4 d/32]: first the codes, two per byte (dim 2i in the low
+    nibble, dim 2i+1 in the high one), then per group the scale and the minimum as little-endian bfloat16."""
+    n, d = codes.shape
+    nib = codes.reshape(n, d // 2, 2)
+    body = (nib[:, :, 0] | (nib[:, :, 1] << 4)).astype(np.uint8)
+    par = np.stack([scale, lo], axis=2).astype(np.float32)       # [n][groups][2]
+    bits = (par.view(np.uint32) >> np.uint32(16)).astype(np.uint16)   # both are bfloat16 values: the low half is zero
+    assert np.array_equal((bits.astype(np.uint32) << np.uint32(16)).view(np.float32), par), "scale/min not bfloat16"
+    tail = np.ascontiguousarray(bits.reshape(n, -1)).astype("<u2").view(np.uint8).reshape(n, -1)
+    return np.concatenate([body, tail], axis=1)
+
+
+def q4_roundtrip(x: np.ndarray):
+    """(dequantized rows float64 [n][d], packed rows uint8) of x [n][d]."""
+    codes, scale, lo = quantize_rows_q4(x)
+    return dequantize_rows_q4(codes, scale, lo), pack_rows_q4(codes, scale, lo)
+
+
+# ----------------------------------------------------------------------------
 # one layer's state and the chunk step
 # ----------------------------------------------------------------------------
 
 class LocretLayerOracle:
     """State = per-KV-head K, V (un-rotated), true scores and original token positions.
 
-    budget: one int for every KV head, or a sequence of h_kv ints (head-wise budgets)."""
+    budget: one int for every KV head, or a sequence of h_kv ints (head-wise budgets).
+    kv_bits: 0 = rows kept as given; 4 = rows quantized to 4 bits when they enter the cache (K, V then hold the
+    dequantized values and Kq, Vq the packed rows)."""
 
     def __init__(self, h: int, h_kv: int, d: int, budget: int, W1, W2, rh_kv_expand: int = 0,
-                 rope: bool = False, theta: float = 10000.0, scale: float | None = None, n_pin: int = 0):
+                 rope: bool = False, theta: float = 10000.0, scale: float | None = None, n_pin: int = 0,
+                 kv_bits: int = 0):
         assert h % h_kv == 0
+        assert kv_bits in (0, 4)
+        self.kv_bits = kv_bits
         self.n_pin = n_pin          # units at the start of the cache that are never evicted (Locret-Q)
         self.h, self.h_kv, self.d, self.g = h, h_kv, d, h // h_kv
         self.budgets = [int(budget)] * h_kv if np.ndim(budget) == 0 else [int(x) for x in budget]
@@ -154,6 +229,9 @@ class LocretLayerOracle:
         self.V = [z(0, self.d) for _ in range(self.h_kv)]
         self.S = [np.zeros(0, dtype=np.float32) for _ in range(self.h_kv)]
         self.P = [np.zeros(0, dtype=np.int64) for _ in range(self.h_kv)]
+        row_bytes = self.d // 2 + 4 * (self.d // Q4_GROUP)
+        self.Kq = [np.zeros((0, row_bytes), dtype=np.uint8) for _ in range(self.h_kv)]
+        self.Vq = [np.zeros((0, row_bytes), dtype=np.uint8) for _ in range(self.h_kv)]
         self.seen = 0
 
     @property
@@ -172,6 +250,10 @@ class LocretLayerOracle:
         k = np.asarray(k, dtype=np.float64)
         v = np.asarray(v, dtype=np.float64)
         T = q.shape[0]
+        if self.kv_bits:
+            # attention reads the cache: the chunk's own rows are seen as they are stored
+            k = np.stack([q4_roundtrip(k[:, m, :])[0] for m in range(self.h_kv)], axis=1)
+            v = np.stack([q4_roundtrip(v[:, m, :])[0] for m in range(self.h_kv)], axis=1)
         out = np.full((T, self.h, self.d), np.nan)
         ts = np.arange(T) if rows is None else np.asarray(rows)
         for j in range(self.h):
@@ -208,8 +290,14 @@ class LocretLayerOracle:
         T = k.shape[0]
         kept_all = []
         for m in range(self.h_kv):
-            Kc = np.concatenate([self.K[m], k[:, m, :]], axis=0)
-            Vc = np.concatenate([self.V[m], v[:, m, :]], axis=0)
+            km, vm = k[:, m, :], v[:, m, :]
+            if self.kv_bits:
+                km, kq = q4_roundtrip(km)
+                vm, vq = q4_roundtrip(vm)
+                Kqc = np.concatenate([self.Kq[m], kq], axis=0)
+                Vqc = np.concatenate([self.Vq[m], vq], axis=0)
+            Kc = np.concatenate([self.K[m], km], axis=0)
+            Vc = np.concatenate([self.V[m], vm], axis=0)
             Sc = np.concatenate([self.S[m], scores[m]])
             Pc = np.concatenate([self.P[m], self.seen + np.arange(T, dtype=np.int64)])
             if evict:
@@ -217,6 +305,8 @@ class LocretLayerOracle:
             else:
                 idx = np.arange(Sc.shape[0], dtype=np.int64)
             self.K[m], self.V[m], self.S[m], self.P[m] = Kc[idx], Vc[idx], Sc[idx], Pc[idx]
+            if self.kv_bits:
+                self.Kq[m], self.Vq[m] = Kqc[idx], Vqc[idx]
             kept_all.append(idx)
         self.seen += T
         if len({len(x) for x in kept_all}) > 1:
