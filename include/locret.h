@@ -74,6 +74,20 @@ typedef struct {
                                 (Section 3.4; pairs (i, i + d/2), inverse frequency theta^(-2i/d)) */
   float   rope_theta;
   float   softmax_scale;  /* 0 selects 1/sqrt(head_dim)                                        */
+  int32_t kv_bits;        /* 0: the cache keeps K and V rows as given
+                             4: 4-bit cache rows (appendix "Orthogonality to Other Methods", the combination
+                                with 4-bit KV-cache quantization).  Every K and V row is quantized when it
+                                enters the cache, per unit and per group of 32 consecutive head dims:
+                                code = clamp(round-half-even((x - lo) / s), 0, 15), lo = the group's minimum,
+                                s = (max - min) / 15 rounded to bf16 (1 for a constant group), in float32;
+                                value = lo + code * s.  K is quantized un-rotated.  Attention (chunk and decode)
+                                reads the cache, so it sees these values, the chunk's own rows included; the
+                                retaining head sees the raw q, k, v.  Packed row: head_dim/2 code bytes (dim 2i
+                                in the low nibble, 2i+1 in the high one), then (s, lo) as little-endian bf16 per
+                                group.  Needs dtype bf16 and head_dim 64, 96 or 128 (LOCRET_ESHAPE); head-wise
+                                budgets are not available with it (LOCRET_ESHAPE).  The two cache copies hold
+                                packed rows only; one bf16 staging copy of the dequantized rows (K rotated)
+                                serves the attention kernels.                                          */
 } locret_config;
 
 /* Bytes of device workspace a context needs (both cache copies, rotated-key shadow, score and
@@ -190,6 +204,14 @@ int64_t locret_tokens_seen(const locret_ctx* ctx);
  * evicts.  Any out-pointer may be NULL. */
 int locret_cache_view(const locret_ctx* ctx, const void** K, const void** V, const float** score,
                       const int32_t** orig_pos, int32_t* len, int32_t* row_stride);
+
+/* 4-bit rows (config.kv_bits = 4): device pointers to the live copy's packed rows, Kq, Vq
+ * [n_kv_heads][row_stride][row_stride_bytes] bytes, of which the first row_bytes = head_dim/2 + 4 head_dim/32 of
+ * every row are the packed row described at locret_config (the rest is padding to a multiple of 16).  With
+ * kv_bits = 4 locret_cache_view returns K = NULL (no un-rotated bf16 keys exist) and V = the dequantized staging
+ * values.  LOCRET_ESTATE without 4-bit rows.  Any out-pointer may be NULL. */
+int locret_cache_view_q4(const locret_ctx* ctx, const void** Kq, const void** Vq, int32_t* len, int32_t* row_stride,
+                         int32_t* row_bytes, int32_t* row_stride_bytes);
 
 /* Per-stage timing for callers that measure (benchmarks, profilers).  locret_profile_enable
  * creates hipEvents for up to max_calls chunk calls (0 disables and frees them); while enabled,

@@ -24,7 +24,7 @@ EXPORTS = [
     "locret_workspace_bytes", "locret_create", "locret_set_weights", "locret_set_pinned_prefix", "locret_reset", "locret_prefill_chunk",
     "locret_score", "locret_decode_step", "locret_evict_compact", "locret_cache_len", "locret_tokens_seen", "locret_cache_view",
     "locret_destroy", "locret_strerror", "locret_profile_mode", "locret_profile_enable", "locret_profile_read",
-    "locret_set_head_budgets", "locret_cache_lens", "locret_score_static",
+    "locret_set_head_budgets", "locret_cache_lens", "locret_score_static", "locret_cache_view_q4",
 ]
 LOCRET_PROF_STAGES = 5
 LOCRET_MAX_HEAD_BUDGETS = 64
@@ -35,7 +35,7 @@ class locret_config(C.Structure):
     _fields_ = [
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("chunk_max", C.c_int32),
         ("budget", C.c_int32), ("d_hidden", C.c_int32), ("rh_kv_expand", C.c_int32), ("dtype", C.c_int32),
-        ("rope_mode", C.c_int32), ("rope_theta", C.c_float), ("softmax_scale", C.c_float),
+        ("rope_mode", C.c_int32), ("rope_theta", C.c_float), ("softmax_scale", C.c_float), ("kv_bits", C.c_int32),
     ]
 
 
@@ -78,6 +78,9 @@ def _load() -> C.CDLL:
     lib.locret_cache_view.restype = C.c_int
     lib.locret_cache_view.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                       C.POINTER(i32), C.POINTER(i32)]
+    lib.locret_cache_view_q4.restype = C.c_int
+    lib.locret_cache_view_q4.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32),
+                                         C.POINTER(i32), C.POINTER(i32)]
     lib.locret_profile_enable.restype = C.c_int
     lib.locret_profile_enable.argtypes = [vp, i32]
     lib.locret_profile_read.restype = C.c_int
@@ -210,6 +213,15 @@ def locret_cache_view(ctx) -> dict:
     return dict(K=K.value, V=V.value, score=S.value, orig_pos=P.value, len=n.value, row_stride=stride.value)
 
 
+def locret_cache_view_q4(ctx) -> dict:
+    Kq, Vq = C.c_void_p(), C.c_void_p()
+    n, stride, rb, rsb = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib.locret_cache_view_q4(ctx, C.byref(Kq), C.byref(Vq), C.byref(n), C.byref(stride), C.byref(rb), C.byref(rsb)),
+           "locret_cache_view_q4")
+    return dict(Kq=Kq.value, Vq=Vq.value, len=n.value, row_stride=stride.value, row_bytes=rb.value,
+                row_stride_bytes=rsb.value)
+
+
 def locret_profile_enable(ctx, max_calls: int) -> None:
     _check(lib.locret_profile_enable(ctx, max_calls), "locret_profile_enable")
 
@@ -230,7 +242,7 @@ def locret_destroy(ctx) -> None:
 def config_from_workload(w) -> locret_config:
     return locret_config(w.h, w.h_kv, w.d, w.B, w.b, w.d_R, w.rh_kv_expand,
                          LOCRET_BF16 if w.dtype == "bf16" else LOCRET_F32, 1 if w.rope else 0,
-                         float(w.theta) if w.rope else 0.0, 0.0)
+                         float(w.theta) if w.rope else 0.0, 0.0, getattr(w, "kv_bits", 0))
 
 
 class LocretLayer:
@@ -314,10 +326,17 @@ class LocretLayer:
             off = addr - base
             raw = self.workspace[off: off + h_kv * stride * inner * esize].view(dtype)
             return raw.view(h_kv, stride, inner)[:, :n].clone()
-        K = grab(view["K"], self.tdtype, d, es)
+        K = grab(view["K"], self.tdtype, d, es) if view["K"] else None
         V = grab(view["V"], self.tdtype, d, es)
         S = grab(view["score"], torch.float32, 1, 4)[..., 0]
         P = grab(view["orig_pos"], torch.int32, 1, 4)[..., 0]
+        if self.cfg.kv_bits:
+            # packed rows instead of K, V: uint8 [h_kv][len][row_bytes] (padding bytes dropped)
+            vq = locret_cache_view_q4(self.ctx)
+            rb, rsb = vq["row_bytes"], vq["row_stride_bytes"]
+            Kq = grab(vq["Kq"], torch.uint8, rsb, 1)[..., :rb].contiguous()
+            Vq = grab(vq["Vq"], torch.uint8, rsb, 1)[..., :rb].contiguous()
+            return Kq, Vq, S, P
         return K, V, S, P
 
     def close(self):

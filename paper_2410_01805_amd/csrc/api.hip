@@ -21,6 +21,7 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
   size_t K[2], V[2], Kr[2], S[2], P[2];
+  size_t Kq[2], Vq[2];      // 4-bit rows: the packed copies; K, V, Kr then all name the one staging pair
   size_t qr, tab, W1t, W2f, part, kept, dpart, apart, total;
   size_t apart_floats;
   size_t zpart, zpart_floats;
@@ -41,6 +42,9 @@ int validate(const locret_config* c) {
   if (!valid_head_dim(c->head_dim)) return LOCRET_ESHAPE;
   if (c->n_q_heads > 1024 || c->d_hidden > 65536) return LOCRET_ESHAPE;
   if ((int64_t)c->budget + c->chunk_max > (int64_t)1 << 28) return LOCRET_ESHAPE;
+  if (c->kv_bits != 0 && c->kv_bits != 4) return LOCRET_EINVAL;
+  // 4-bit rows: bf16 tensors on the matrix-core attention kernels (which rotate the queries themselves)
+  if (c->kv_bits == 4 && !(c->dtype == LOCRET_BF16 && q4_head_dim(c->head_dim))) return LOCRET_ESHAPE;
   return LOCRET_OK;
 }
 
@@ -74,6 +78,7 @@ void fill_dims(const locret_config* c, Dims* D) {
   D->rope = c->rope_mode;
   D->K = (D->h + 2 * D->h_kv) * D->d;
   D->d_R = c->d_hidden;
+  D->kv_bits = c->kv_bits;
 }
 
 int max_score_parts(const Dims& D) {
@@ -86,12 +91,25 @@ void make_layout(const locret_config* c, const Dims& D, Layout* L) {
   const size_t rows = (size_t)D.h_kv * D.cap;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += up(bytes); return o; };
-  for (int i = 0; i < 2; ++i) {
-    L->K[i] = take(rows * D.d * es);
-    L->V[i] = take(rows * D.d * es);
-    L->Kr[i] = D.rope ? take(rows * D.d * es) : 0;
-    L->S[i] = take(rows * sizeof(float));
-    L->P[i] = take(rows * sizeof(int32_t));
+  if (D.kv_bits == 4) {
+    const size_t kst = take(rows * D.d * es), vst = take(rows * D.d * es);      // the staging pair
+    for (int i = 0; i < 2; ++i) {
+      L->K[i] = L->Kr[i] = kst;
+      L->V[i] = vst;
+      L->Kq[i] = take(rows * q4_row_stride(D.d));
+      L->Vq[i] = take(rows * q4_row_stride(D.d));
+      L->S[i] = take(rows * sizeof(float));
+      L->P[i] = take(rows * sizeof(int32_t));
+    }
+  } else {
+    for (int i = 0; i < 2; ++i) {
+      L->K[i] = take(rows * D.d * es);
+      L->V[i] = take(rows * D.d * es);
+      L->Kr[i] = D.rope ? take(rows * D.d * es) : 0;
+      L->S[i] = take(rows * sizeof(float));
+      L->P[i] = take(rows * sizeof(int32_t));
+      L->Kq[i] = L->Vq[i] = 0;
+    }
   }
   L->qr = D.rope ? take((size_t)c->chunk_max * D.h * D.d * es) : 0;
   L->tab = D.rope ? take((size_t)D.cap * (D.d / 2) * sizeof(float2)) : 0;
@@ -188,9 +206,14 @@ struct locret_ctx {
     CacheBuf b;
     b.K = ws + L.K[i];
     b.V = ws + L.V[i];
-    b.Kr = D.rope ? ws + L.Kr[i] : nullptr;
+    b.Kr = (D.rope || D.kv_bits) ? ws + L.Kr[i] : nullptr;
     b.S = (float*)(ws + L.S[i]);
     b.P = (int32_t*)(ws + L.P[i]);
+    if (D.kv_bits) {
+      b.Kq = ws + L.Kq[i];
+      b.Vq = ws + L.Vq[i];
+      b.qstride = q4_row_stride(D.d);
+    }
     return b;
   }
 };
@@ -229,6 +252,7 @@ int locret_create(const locret_config* cfg, void* ws, size_t bytes, locret_ctx**
   const int d = cfg->head_dim;
   c->mfma_attn = !simple && c->D.bf16 && (d == 64 || d == 96 || d == 128);
   c->mfma_score = !simple && c->D.bf16 && score_parts_bf16(c->D) > 0;
+  if (c->D.kv_bits && !c->mfma_attn) { delete c; return LOCRET_ESHAPE; }   // 4-bit rows: matrix-core attention only
   if (c->D.rope) {
     launch_rope_table((float2*)(c->ws + c->L.tab), c->D.cap, c->D.d, cfg->rope_theta, 0);
     if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) { delete c; return LOCRET_EHIP; }
@@ -277,7 +301,7 @@ int locret_set_head_budgets(locret_ctx* c, const int32_t* budgets) {
   if (!c) return LOCRET_EINVAL;
   if (c->n_c != 0) return LOCRET_ESTATE;
   if (!budgets) { c->ragged = 0; return LOCRET_OK; }
-  if (c->D.h_kv > MAX_HEAD_BUDGETS) return LOCRET_ESHAPE;
+  if (c->D.h_kv > MAX_HEAD_BUDGETS || c->D.kv_bits) return LOCRET_ESHAPE;
   for (int m = 0; m < c->D.h_kv; ++m)
     if (budgets[m] < 1 || budgets[m] > c->cfg.budget) return LOCRET_EINVAL;
   for (int m = 0; m < c->D.h_kv; ++m) { c->b_h[m] = budgets[m]; c->n_c_h[m] = 0; }
@@ -359,8 +383,9 @@ static void run_evict(locret_ctx* c, int L, int n_stab, int32_t* kept_idx_out, h
   }
   if (over) {
     CacheBuf B = c->buf(c->cur ^ 1);
-    launch_compact(c->D, A, B, a.kept, b, a.n_keep, c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr, st,
-                   c->ragged ? &a.keep_h : nullptr);
+    const float2* tab = c->D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
+    if (c->D.kv_bits) launch_compact_q4(c->D, A, B, a.kept, b, a.n_keep, tab, st);
+    else launch_compact(c->D, A, B, a.kept, b, a.n_keep, tab, st, c->ragged ? &a.keep_h : nullptr);
     c->cur ^= 1;
   }
   c->mark(4, 1, st);
@@ -397,7 +422,8 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
   HeadLens hl_tmp;
   const HeadLens* hl = c->lens(&hl_tmp);      // per-head cache lengths before this chunk, or NULL
   c->mark(0, 0, st);
-  launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st, false, hl);
+  if (D.kv_bits) launch_append_q4(D, k, v, T, c->n_c, c->seen, A, tab, st, false);
+  else launch_append(D, fused_q ? nullptr : q, k, v, T, c->n_c, c->seen, A, qr, tab, st, false, hl);
   c->mark(0, 1, st);
   const void* qx = (D.rope && !fused_q) ? qr : q;
   const void* Kx = D.rope ? A.Kr : A.K;
@@ -488,8 +514,10 @@ int locret_decode_step(locret_ctx* c, const void* q, const void* k, const void* 
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   HeadLens hl_tmp;
   if (with_score) run_score(c, q, k, v, 1, A.S, c->n_c, scores_out, st);
+  // 4-bit rows: the token enters the cache first (packed row + staging), then attention reads it like any unit
+  if (D.kv_bits) launch_append_q4(D, k, v, 1, c->n_c, c->seen, A, tab, st, /*mark_unscored=*/!with_score);
   launch_decode_step(D, q, k, v, A, tab, attn_out, c->n_c, c->seen, c->scale, (float*)(c->ws + c->L.dpart), st,
-                     /*mark_unscored=*/!with_score, c->lens(&hl_tmp));
+                     /*mark_unscored=*/!with_score, c->lens(&hl_tmp), /*pre_appended=*/D.kv_bits != 0);
   grow(c, 1);
   c->seen += 1;
   return hipGetLastError() == hipSuccess ? LOCRET_OK : LOCRET_EHIP;
@@ -533,7 +561,8 @@ int locret_evict_compact(locret_ctx* c, const float* chunk_scores, const void* k
   const float2* tab = D.rope ? (const float2*)(c->ws + c->L.tab) : nullptr;
   HeadLens hl_tmp;
   const HeadLens* hl = c->lens(&hl_tmp);
-  launch_append(D, nullptr, k, v, T, c->n_c, c->seen, A, nullptr, tab, st, false, hl);
+  if (D.kv_bits) launch_append_q4(D, k, v, T, c->n_c, c->seen, A, tab, st, false);
+  else launch_append(D, nullptr, k, v, T, c->n_c, c->seen, A, nullptr, tab, st, false, hl);
   launch_score_reduce(chunk_scores, 1, T, D.h_kv, T, A.S, D.cap, c->n_c, nullptr, st, hl);
   run_evict(c, c->n_c + T, n_stab, kept_idx_out, st);
   c->seen += T;
@@ -552,12 +581,26 @@ int locret_cache_view(const locret_ctx* c, const void** K, const void** V, const
                       const int32_t** orig_pos, int32_t* len, int32_t* row_stride) {
   if (!c) return LOCRET_EINVAL;
   CacheBuf A = c->buf(c->cur);
-  if (K) *K = A.K;
+  if (K) *K = c->D.kv_bits ? nullptr : A.K;       // 4-bit rows: no un-rotated bf16 keys exist (locret_cache_view_q4)
   if (V) *V = A.V;
   if (score) *score = A.S;
   if (orig_pos) *orig_pos = A.P;
   if (len) *len = c->n_c;
   if (row_stride) *row_stride = c->D.cap;
+  return LOCRET_OK;
+}
+
+int locret_cache_view_q4(const locret_ctx* c, const void** Kq, const void** Vq, int32_t* len, int32_t* row_stride,
+                         int32_t* row_bytes, int32_t* row_stride_bytes) {
+  if (!c) return LOCRET_EINVAL;
+  if (!c->D.kv_bits) return LOCRET_ESTATE;
+  CacheBuf A = c->buf(c->cur);
+  if (Kq) *Kq = A.Kq;
+  if (Vq) *Vq = A.Vq;
+  if (len) *len = c->n_c;
+  if (row_stride) *row_stride = c->D.cap;
+  if (row_bytes) *row_bytes = q4_row_bytes(c->D.d);
+  if (row_stride_bytes) *row_stride_bytes = A.qstride;
   return LOCRET_OK;
 }
 

@@ -42,6 +42,7 @@ struct DecodeToken {
   float* S;
   int32_t* P;
   int g, cap, n_c, seen, mark_unscored;
+  int pre;                // 1: the token is already at slot n_c; attend over n_c + 1 units, no token workgroup
   float c_log2;
   HeadLens n_c_h;         // units per head before the token (ragged), else n_c
 };
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
   // read, the partial carries max -inf and sum 0, which the merge weighs with 0)
   const int n_keys = head_len(tk.n_c_h, m, tk.n_c);   // units of this head in the cache = the new token's slot and position
   const int k0 = split * keys_per_wg;
-  const int k1 = min(n_keys, k0 + keys_per_wg);
+  const int k1 = min(n_keys + tk.pre, k0 + keys_per_wg);
   const T* Kb = Kx + (int64_t)m * cap * D;
   const T* Vb = V + (int64_t)m * cap * D;
   const int off = (act ? sub : 0) * VEC;
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
     }
   }
   __syncthreads();
-  const bool token_wg = split == n_splits - 1;
+  const bool token_wg = !tk.pre && split == n_splits - 1;
   for (int idx = tid; idx < G * PW && !token_wg; idx += DEC_THREADS) {
     const int u = idx / PW, e = idx % PW;
     if (g0 + u >= g) continue;
@@ -361,9 +362,10 @@ int decode_max_splits(const Dims& D) {
 template <typename T, int DD>
 static void decode_launch(const Dims& D, const DecodeToken& tk, T* out, float* part, hipStream_t st) {
   const int kpw = decode_keys_per_split(D, tk.n_c);
-  const int n_attn = (tk.n_c + kpw - 1) / kpw;            // splits over the units already in the cache (the longest head's)
+  const int n_attn = (tk.n_c + tk.pre + kpw - 1) / kpw;   // splits over the units already in the cache (the longest head's)
   const T* Kx = (const T*)(D.rope ? tk.Kr : tk.K);
-  const dim3 grid(n_attn + 1, D.h_kv);                    // + the workgroup of the new token
+  const int n_part = n_attn + (tk.pre ? 0 : 1);           // + the workgroup of the new token
+  const dim3 grid(n_part, D.h_kv);
   for (int g0 = 0; g0 < D.g; g0 += 4) {
     const int left = D.g - g0;
     if (left >= 3)
@@ -373,14 +375,15 @@ static void decode_launch(const Dims& D, const DecodeToken& tk, T* out, float* p
     else
       hipLaunchKernelGGL((decode_attn_kernel<T, DD, 1>), grid, dim3(DEC_THREADS), 0, st, Kx, g0, kpw, part, tk);
   }
-  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, (const float*)part, n_attn + 1, D.d,
+  hipLaunchKernelGGL(decode_merge_kernel<T>, dim3(D.h), dim3(DEC_MERGE_THREADS), 0, st, (const float*)part, n_part, D.d,
                      out);
 }
 
 void launch_decode_step(const Dims& D, const void* q, const void* k, const void* v, const CacheBuf& c,
                         const float2* tab, void* out, int n_c, int64_t seen, float scale, float* part, hipStream_t st,
-                        bool mark_unscored, const HeadLens* n_c_h) {
+                        bool mark_unscored, const HeadLens* n_c_h, bool pre_appended) {
   DecodeToken tk;
+  tk.pre = pre_appended ? 1 : 0;
   tk.q = q; tk.k = k; tk.v = v;
   tk.tab = D.rope ? tab : nullptr;
   tk.K = c.K; tk.V = c.V; tk.Kr = c.Kr; tk.S = c.S; tk.P = c.P;

@@ -92,6 +92,7 @@ struct Dims {
   int rope;     // rotary mode
   int K;        // retaining-head input width after folding: (h + 2 h_kv) d
   int d_R;      // retaining-head hidden width
+  int kv_bits;  // 0: cache rows in the storage type; 4: packed 4-bit rows plus one bf16 staging copy (quant_rows.hip)
 };
 
 // One copy of the cache (the library ping-pongs between two).
@@ -101,6 +102,12 @@ struct CacheBuf {
   void* Kr;      // [h_kv][cap][d] keys rotated to their slot position (rope only, else NULL)
   float* S;      // [h_kv][cap] true scores
   int32_t* P;    // [h_kv][cap] original token index
+  // 4-bit rows (Dims::kv_bits = 4): Kq, Vq [h_kv][cap][qstride bytes] are this copy's packed rows; K, Kr and V then
+  // all point at the single bf16 staging arrays that both copies share (K = Kr = dequantized keys, rotated to
+  // their slot when rope is on; V = dequantized values).
+  void* Kq = nullptr;
+  void* Vq = nullptr;
+  int qstride = 0;
 };
 
 // tab[pos][i] = (cos, sin)(pos * theta^(-2i/d)), angles formed in double.
@@ -117,6 +124,17 @@ void launch_prep_weights(const Dims& D, int expand, const void* W1, const void* 
 void launch_append(const Dims& D, const void* q, const void* k, const void* v, int T, int n_c,
                    int64_t seen, const CacheBuf& c, void* qr, const float2* tab, hipStream_t st,
                    bool mark_unscored = false, const HeadLens* n_c_h = nullptr);
+
+// 4-bit rows.  Append: quantize the chunk's k, v rows into the packed arrays of `c` at slots [n_c, n_c+T) and write
+// their dequantized values (K rotated to n_c+t) into the staging arrays; P and optional NaN scores as launch_append.
+// Compact: dst packed rows r = src packed rows kept[m][r], S, P likewise, staging rows r rewritten for slot r.
+bool q4_head_dim(int d);
+int q4_row_bytes(int d);      // d/2 code bytes + 4 bytes (scale, minimum as bf16) per group of 32 dims
+int q4_row_stride(int d);     // the same, padded to a multiple of 16
+void launch_append_q4(const Dims& D, const void* k, const void* v, int T, int n_c, int64_t seen, const CacheBuf& c,
+                      const float2* tab, hipStream_t st, bool mark_unscored);
+void launch_compact_q4(const Dims& D, const CacheBuf& src, const CacheBuf& dst, const int32_t* kept, int kept_stride,
+                       int n_keep, const float2* tab, hipStream_t st);
 
 // Attention of T queries (already rotated if rope) over slots [0, n_c+T) of Kx/V, query t seeing
 // slots <= n_c+t (Eq. 1).  Reference-grade VALU kernel, any storage type.
@@ -153,9 +171,11 @@ bool attention_bf16_attaches_timer(const Dims& D);
 // `part` holds h * decode_max_splits(D) * (d + 2) floats of split-K partials.
 int decode_keys_per_split(const Dims& D, int n_keys);
 int decode_max_splits(const Dims& D);
+// pre_appended: the token already sits at slot n_c of the arrays (4-bit rows: launch_append_q4 put it there as the
+// cache stores it); the launch then attends over n_c + 1 units and appends nothing.
 void launch_decode_step(const Dims& D, const void* q, const void* k, const void* v, const CacheBuf& c,
                         const float2* tab, void* out, int n_c, int64_t seen, float scale, float* part, hipStream_t st,
-                        bool mark_unscored, const HeadLens* n_c_h = nullptr);
+                        bool mark_unscored, const HeadLens* n_c_h = nullptr, bool pre_appended = false);
 
 // Retaining head: partial scores part[nb][h_kv][T] over hidden-unit blocks; returns the number of
 // blocks nb through *n_parts.  `part` must hold (d_R/score_part_width) * h_kv * chunk_max floats.

@@ -46,6 +46,7 @@ class Workload:
     planted_frac: float = 0.0   # fraction of positions whose keys are scaled
     planted_scale: float = 1.0
     w_std: float = 0.02
+    kv_bits: int = 0            # 0: cache rows as given; 4: 4-bit cache rows
 
     @property
     def g(self) -> int:
