@@ -224,8 +224,11 @@ int locret_cache_view_q4(const locret_ctx* ctx, const void** Kq, const void** Vq
  * slows a step by about 3 %.  locret_profile_mode(ctx, 1) times the attention kernel only, through
  * its own dispatch (no extra packets in the stream: the step runs at full speed); the other entries
  * of stage_ms are then 0, and if the attention kernel in use cannot be timed that way *n_calls is 0.
- * Mode 0 (default) times every stage.  The mode can be changed while no recorded call is unread
- * (LOCRET_ESTATE otherwise). */
+ * Mode 0 (default) times every stage with events between the kernels.  Mode 2 times every stage through the
+ * dispatches of its own kernels (first kernel's begin to last kernel's end; no extra packets, so the figures are
+ * pure kernel durations, as a profiler's kernel trace reports them; where the selection rides in the attention
+ * launch its entry is 0 and the attention entry covers it).  The mode can be changed while no recorded call is
+ * unread (LOCRET_ESTATE otherwise). */
 #define LOCRET_PROF_STAGES 5
 int locret_profile_mode(locret_ctx* ctx, int32_t mode);
 int locret_profile_enable(locret_ctx* ctx, int32_t max_calls);

@@ -14,6 +14,10 @@
 
 using namespace locret;
 
+namespace locret {
+thread_local StageTimer* tl_stage_timer = nullptr;
+}
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -197,10 +201,26 @@ struct locret_ctx {
   int overlap;
   std::vector<hipEvent_t> ev;   // profiling: a (begin, end) pair per stage per recorded call
   int prof_max, prof_calls;
-  int prof_mode;    // 0: every stage (event packets between the kernels), 1: attention only (no extra packets)
+  int prof_mode;    // 0: every stage (event packets between the kernels), 1: attention only (no extra packets),
+                    // 2: every stage through the kernels' own dispatches (no extra packets)
+  std::vector<uint8_t> prof_launched;   // mode 2: per recorded call, bit s set when stage s launched a kernel
+  StageTimer stage_timer;
   hipEvent_t prof_event(int stage, int end) { return ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end]; }
   void mark(int stage, int end, hipStream_t st) {
-    if (prof_calls < prof_max && prof_mode == 0) (void)hipEventRecord(ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end], st);
+    if (prof_calls >= prof_max) return;
+    if (prof_mode == 0) (void)hipEventRecord(ev[((size_t)prof_calls * LOCRET_PROF_STAGES + stage) * 2 + end], st);
+    if (prof_mode == 2) {
+      // the launches between mark(stage, 0) and mark(stage, 1) carry the stage's events themselves
+      if (end == 0) {
+        stage_timer.start = prof_event(stage, 0);
+        stage_timer.stop = prof_event(stage, 1);
+        stage_timer.launches = 0;
+        tl_stage_timer = &stage_timer;
+      } else {
+        if (stage_timer.launches > 0) prof_launched[prof_calls] |= (uint8_t)(1u << stage);
+        tl_stage_timer = nullptr;
+      }
+    }
   }
   CacheBuf buf(int i) const {
     CacheBuf b;
@@ -439,6 +459,7 @@ int locret_prefill_chunk(locret_ctx* c, const void* q, const void* k, const void
       tm.stop = c->prof_event(1, 1);
       launch_attention_bf16(D, qx, Kx, A.V, attn_out, T, n_c, c->scale, st, fused_q ? tab : nullptr, tm, sel, hl,
                             split_part, c->L.apart_floats);
+      if (c->prof_mode == 2) c->prof_launched[c->prof_calls] |= 1u << 1;
       return;
     }
     c->mark(1, 0, st);
@@ -622,11 +643,12 @@ int locret_profile_enable(locret_ctx* c, int32_t max_calls) {
     c->ev.push_back(e);
   }
   c->prof_max = max_calls;
+  c->prof_launched.assign((size_t)max_calls, 0);
   return LOCRET_OK;
 }
 
 int locret_profile_mode(locret_ctx* c, int32_t mode) {
-  if (!c || (mode != 0 && mode != 1)) return LOCRET_EINVAL;
+  if (!c || mode < 0 || mode > 2) return LOCRET_EINVAL;
   if (c->prof_calls != 0) return LOCRET_ESTATE;       // read or re-arm first
   c->prof_mode = mode;
   return LOCRET_OK;
@@ -646,6 +668,7 @@ int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
     hipEvent_t* e = &c->ev[(size_t)i * LOCRET_PROF_STAGES * 2];
     for (int s = 0; s < LOCRET_PROF_STAGES; ++s) {
       if (attn_only && s != 1) continue;
+      if (c->prof_mode == 2 && !(c->prof_launched[i] & (1u << s))) continue;     // the stage launched nothing
       float ms = 0.f;
       if (hipEventSynchronize(e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;
       if (hipEventElapsedTime(&ms, e[2 * s], e[2 * s + 1]) != hipSuccess) return LOCRET_EHIP;
@@ -653,6 +676,7 @@ int locret_profile_read(locret_ctx* c, double* stage_ms, int32_t* n_calls) {
     }
   }
   c->prof_calls = 0;
+  std::fill(c->prof_launched.begin(), c->prof_launched.end(), (uint8_t)0);
   return LOCRET_OK;
 }
 

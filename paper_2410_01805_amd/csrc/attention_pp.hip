@@ -104,7 +104,8 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
   // of microseconds, long before the attention workgroups that follow it on the same CU would have started
   // their second round; the selection's latency disappears from the step.
   if ((int)blockIdx.x < n_sel) {
-    select_reg_body<PP_SEL_MAXR, PP_NW * 64>(sel, blockIdx.x, (uint32_t*)ring);
+    select_reg_body<PP_SEL_MAXR, PP_NW * 64, 4>(sel, blockIdx.x, (uint32_t*)ring);
+    static_assert(select_body_smem_words(PP_NW * 64, 4) * 4 <= (int)sizeof(ring), "the selection's scratch fits the ring");
     return;
   }
   const int bid = blockIdx.x - n_sel;

@@ -153,11 +153,11 @@ void launch_append(const Dims& D, const void* q, const void* k, const void* v, i
   int64_t threads = (int64_t)T * (q_rows + 2 * D.h_kv) * tpr;
   dim3 grid((unsigned)((threads + 255) / 256));
   if (D.bf16)
-    hipLaunchKernelGGL(append_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+    launch_kernel(append_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (bf16_t*)c.K, (bf16_t*)c.V,
                        (bf16_t*)c.Kr, c.P, (bf16_t*)qr, tab, D.rope, q_rows, Su, hl);
   else
-    hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
+    launch_kernel(append_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
                        (const float*)v, T, n_c, (int)seen, D.h, D.h_kv, D.d, D.cap, (float*)c.K, (float*)c.V,
                        (float*)c.Kr, c.P, (float*)qr, tab, D.rope, q_rows, Su, hl);
 }
@@ -270,7 +270,7 @@ void launch_compact(const Dims& D, const CacheBuf& s, const CacheBuf& t, const i
   dim3 grid(gx, (unsigned)((D.h_kv + hpb - 1) / hpb));
   // two heads per batch: enough loads in flight per thread while registers still allow many wavefronts
 #define LOCRET_COMPACT(TT, RG)                                                                                   \
-  hipLaunchKernelGGL((compact_kernel<TT, 2, RG>), grid, dim3(256), 0, st, (const TT*)s.K, (const TT*)s.V, s.S, s.P, \
+  launch_kernel((compact_kernel<TT, 2, RG>), grid, dim3(256), 0, st, (const TT*)s.K, (const TT*)s.V, s.S, s.P, \
                      (TT*)t.K, (TT*)t.V, (TT*)t.Kr, t.S, t.P, kept, kept_stride, n_keep, D.h_kv, D.d, D.cap, tab,   \
                      D.rope, hpb, hl)
   if (D.bf16) { if (hl.ragged) LOCRET_COMPACT(bf16_t, true); else LOCRET_COMPACT(bf16_t, false); }

@@ -2,6 +2,7 @@
 // Not part of the public boundary (include/locret.h is).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace locret {
@@ -13,6 +14,29 @@ struct LaunchTimer {
   hipEvent_t start = nullptr;
   hipEvent_t stop = nullptr;
 };
+
+// Stage timer for the launchers that take no LaunchTimer.  While the host code has one set (around one stage of a
+// step, on the calling thread), every launch made through launch_kernel goes out with events attached to its own
+// dispatch: `start` with the first launch of the stage only, `stop` with each (the last launch's is the one
+// read).  Null: plain launches.
+struct StageTimer {
+  hipEvent_t start = nullptr;
+  hipEvent_t stop = nullptr;
+  int launches = 0;
+};
+extern thread_local StageTimer* tl_stage_timer;
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem, hipStream_t st, Args... args) {
+  StageTimer* t = tl_stage_timer;
+  if (t) {
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, st, t->launches == 0 ? t->start : nullptr, t->stop, 0,
+                          static_cast<KArgs>(args)...);
+    t->launches++;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, shmem, st, static_cast<KArgs>(args)...);
+  }
+}
 
 // Head-wise budgets (appendix "Orthogonality to Other Methods", head-wise budget allocation: KV heads evict
 // independently, so each may have its own budget): the heads' caches then differ in length.  Kernels take

@@ -123,7 +123,7 @@ void launch_append_q4(const Dims& D, const void* k, const void* v, int T, int n_
   const dim3 grid((unsigned)((rows + 3) / 4));
   float* Su = mark_unscored ? c.S : nullptr;
 #define LOCRET_Q4A(DD)                                                                                              \
-  hipLaunchKernelGGL(append_q4_kernel<DD>, grid, dim3(256), 0, st, (const bf16_t*)k, (const bf16_t*)v, T, n_c,       \
+  launch_kernel(append_q4_kernel<DD>, grid, dim3(256), 0, st, (const bf16_t*)k, (const bf16_t*)v, T, n_c,       \
                      (int)seen, D.h_kv, D.cap, (uint8_t*)c.Kq, (uint8_t*)c.Vq, c.qstride, (bf16_t*)c.Kr, (bf16_t*)c.V, \
                      c.P, D.rope ? tab : nullptr, Su)
   if (D.d == 128) LOCRET_Q4A(128); else if (D.d == 96) LOCRET_Q4A(96); else LOCRET_Q4A(64);
@@ -136,7 +136,7 @@ void launch_compact_q4(const Dims& D, const CacheBuf& s, const CacheBuf& t, cons
   if (rows == 0) return;
   const dim3 grid((unsigned)((rows + 3) / 4));
 #define LOCRET_Q4C(DD)                                                                                              \
-  hipLaunchKernelGGL(compact_q4_kernel<DD>, grid, dim3(256), 0, st, (const uint8_t*)s.Kq, (const uint8_t*)s.Vq, s.S,  \
+  launch_kernel(compact_q4_kernel<DD>, grid, dim3(256), 0, st, (const uint8_t*)s.Kq, (const uint8_t*)s.Vq, s.S,  \
                      s.P, (uint8_t*)t.Kq, (uint8_t*)t.Vq, t.S, t.P, (bf16_t*)t.Kr, (bf16_t*)t.V, kept, kept_stride,    \
                      n_keep, D.h_kv, D.cap, s.qstride, D.rope ? tab : nullptr)
   if (D.d == 128) LOCRET_Q4C(128); else if (D.d == 96) LOCRET_Q4C(96); else LOCRET_Q4C(64);

@@ -377,16 +377,16 @@ int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v
     if (n_z < 1) n_z = 1;
   }
   if (n_z == 1) {
-    hipLaunchKernelGGL(score_mfma_kernel<false>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+    launch_kernel(score_mfma_kernel<false>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T,
                        (float*)nullptr, D.d_R);
     return D.d_R / RT_M;
   }
   grid.z = n_z;
-  hipLaunchKernelGGL(score_mfma_kernel<true>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+  launch_kernel(score_mfma_kernel<true>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                      (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T, zpart,
                      D.d_R);
-  hipLaunchKernelGGL(score_finish_kernel, dim3(T), dim3(FIN_THREADS), 0, st, (const float*)zpart, n_z, T, D.d_R, W2f,
+  launch_kernel(score_finish_kernel, dim3(T), dim3(FIN_THREADS), 0, st, (const float*)zpart, n_z, T, D.d_R, W2f,
                      D.h_kv, part, T);
   return 1;
 }

@@ -167,8 +167,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
 // Register-resident variant: MAXR keys per thread (select_body.h).
 template <int MAXR>
 __global__ __launch_bounds__(SEL_THREADS) void select_reg_kernel(SelectArgs a) {
-  __shared__ uint32_t smem[select_body_smem_words(SEL_THREADS)];
-  select_reg_body<MAXR, SEL_THREADS>(a, blockIdx.x, smem);
+  __shared__ __attribute__((aligned(16))) uint32_t smem[select_body_smem_words(SEL_THREADS, 2)];
+  select_reg_body<MAXR, SEL_THREADS, 2>(a, blockIdx.x, smem);
 }
 
 // bytes of dynamic LDS the in-LDS variant may use: asked for once (thread-safe static initialisation)
@@ -199,18 +199,18 @@ void launch_select(const SelectArgs& a, int h_kv, hipStream_t st) {
   const int n_cand = a.L - ns - npin;
   const int wseg = ((n_cand + SEL_WAVES - 1) / SEL_WAVES + 63) & ~63;
   if (wseg <= 12 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
+    launch_kernel(select_reg_kernel<12>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;
   }
   if (wseg <= 24 * 64) {
-    hipLaunchKernelGGL(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
+    launch_kernel(select_reg_kernel<24>, dim3(h_kv), dim3(SEL_THREADS), 0, st, a);
     return;
   }
   size_t need = (size_t)(SEL_HDR + n_cand) * sizeof(uint32_t);
   if (need <= (size_t)lds_limit())
-    hipLaunchKernelGGL(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, a);
+    launch_kernel(select_kernel<true>, dim3(h_kv), dim3(SEL_THREADS), need, st, a);
   else
-    hipLaunchKernelGGL(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, a);
+    launch_kernel(select_kernel<false>, dim3(h_kv), dim3(SEL_THREADS), SEL_HDR * sizeof(uint32_t), st, a);
 }
 
 }  // namespace locret

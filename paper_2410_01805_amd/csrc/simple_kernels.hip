@@ -222,10 +222,10 @@ void launch_score_simple(const Dims& D, const void* q, const void* k, const void
   dim3 grid((T + SC_TM - 1) / SC_TM, (D.d_R + SC_TN - 1) / SC_TN);
   const int hd = D.h * D.d, kvd = D.h_kv * D.d;
   if (D.bf16)
-    hipLaunchKernelGGL(score_simple_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
+    launch_kernel(score_simple_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)q, (const bf16_t*)k,
                        (const bf16_t*)v, T, hd, kvd, (const bf16_t*)W1t, W2f, D.K, D.d_R, D.h_kv, part, T);
   else
-    hipLaunchKernelGGL(score_simple_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
+    launch_kernel(score_simple_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
                        (const float*)v, T, hd, kvd, (const float*)W1t, W2f, D.K, D.d_R, D.h_kv, part, T);
 }
 
@@ -245,7 +245,7 @@ __global__ void score_reduce_kernel(const float* __restrict__ part, int n_parts,
 void launch_score_reduce(const float* part, int n_parts, int part_T, int h_kv, int T, float* S, int cap, int n_c,
                          float* out, hipStream_t st, const HeadLens* n_c_h) {
   int n = h_kv * T;
-  hipLaunchKernelGGL(score_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, n_parts, part_T, h_kv, T,
+  launch_kernel(score_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, n_parts, part_T, h_kv, T,
                      S, cap, n_c, out, head_lens_or_common(n_c_h));
 }
 

@@ -277,24 +277,27 @@ def test_profile_modes():
     w = synth.tiny(name="prof", dtype="bf16", h=8, h_kv=2, d=128, N=1200, B=300, b=700, n_s=50, d_R=128)
     layer, _, _ = make_layer(w)
     chunks = [tuple(dev(x, w) for x in synth.chunk(w, c)) for c in range(4)]
-    for mode in (0, 1):
+    for mode in (0, 1, 2):
         layer.reset()
         B.locret_profile_mode(layer.ctx, mode)
         B.locret_profile_enable(layer.ctx, 3)            # the 4th call is not recorded
         for q, k, v in chunks:
             layer.prefill_chunk(q, k, v, w.n_s)
         with pytest.raises(B.LocretError) as e:          # recorded calls are still unread
-            B.locret_profile_mode(layer.ctx, 1 - mode)
+            B.locret_profile_mode(layer.ctx, (mode + 1) % 3)
         assert e.value.code == B.LOCRET_ESTATE
         ms, n = B.locret_profile_read(layer.ctx)
         assert n == 3 and 0.0 < ms[1] < 50.0             # attention was timed
         if mode == 0:
             assert all(x > 0.0 for x in ms)              # every stage (compaction ran from the third chunk on)
-        else:
+        elif mode == 1:
             assert ms[0] == ms[2] == ms[3] == ms[4] == 0.0
+        else:
+            # through the kernels' own dispatches: the selection rides in the attention launch here, so its entry is 0
+            assert ms[0] > 0.0 and ms[2] > 0.0 and ms[4] > 0.0 and ms[3] == 0.0
         B.locret_profile_enable(layer.ctx, 0)
     with pytest.raises(B.LocretError):
-        B.locret_profile_mode(layer.ctx, 2)
+        B.locret_profile_mode(layer.ctx, 3)
     layer.close()
 
 
