@@ -5,9 +5,15 @@
 // Split-K over the key axis: workgroup (split, m) owns DEC_KEYS keys of KV head m and serves the
 // query heads of its group (G at a time).  A key row is spread over LPR lanes (16 bytes per lane,
 // padded to a power of two), so one load instruction of a wavefront fetches 64 / LPRP whole rows,
-// contiguous in memory.  Each lane keeps the query values of its own dims for G heads; a logit is G
-// short dot products plus a butterfly over the lanes of the row; the lanes of a row then share the
-// probability and accumulate p * v for their dims.  Online softmax with a lazily raised max as in
+// contiguous in memory.  Logits: with bf16 storage and head dims that are multiples of 32 the wavefront's 16
+// (or 32) rows of an iteration form one S^T = K Q^T product on the matrix cores (v_mfma_f32_16x16x32_bf16:
+// rows = keys, fetched from memory straight into the A-operand layout; columns = the G query heads, padded to
+// 16), and the logits reach the lanes that own the rows through 256 bytes of LDS per wavefront; the matrix cores
+// idle most of the time here, but the G dot products per row with their butterflies over the row's lanes were
+// more than half of the vector instructions and kept the kernel from overlapping them with its loads.  Other
+// types: each lane keeps the query values of its own dims for G heads and a logit is G short dot products plus a
+// butterfly over the lanes of the row.  Either way the lanes of a row then share the probability and accumulate
+// p * v for their dims.  Online softmax with a lazily raised max as in
 // the prefill kernels, one decision per UN rows.  The (max, sum, vector) triples of the 16 or 32
 // row slots of a workgroup are merged through LDS, those of the splits by decode_merge_kernel.
 //
@@ -18,7 +24,9 @@
 // combines the partials.  A separate append launch cost 15 % of the step.
 #include <stdlib.h>
 
-#include "device_util.h"
+#include <type_traits>
+
+#include "attn_common.h"
 #include "kernels.h"
 
 namespace locret {
@@ -66,6 +74,12 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
   typedef Vec16<T> V16;
   typedef decltype(V16().raw) raw_t;
   __shared__ float sets[NSETS * G * PW];
+  // logits on the matrix cores (see the file header)
+  constexpr bool MM = std::is_same<T, bf16_t>::value && D % 32 == 0 && G <= 16 && (DEC_UN * KPW) % 16 == 0;
+  constexpr int WROWS = DEC_UN * KPW;                // rows of a wavefront per iteration
+  constexpr int NSB = MM ? WROWS / 16 : 1;           // 16-row blocks among them
+  constexpr int NKS = MM ? D / 32 : 1;               // contraction steps
+  __shared__ float slog[MM ? (DEC_THREADS / 64) * WROWS * G : 1];
 
   const int split = blockIdx.x, m = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -119,6 +133,28 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
 #pragma unroll
       for (int e = 0; e < VEC; ++e) qv[u][e] = act ? x.get(e) * c_log2 : 0.f;   // logits in log2 units
     }
+    if (MM) {                                          // the matrix-core path takes the query from LDS
+      if (act && grp == 0 && wave == 0)
+#pragma unroll
+        for (int u = 0; u < G; ++u)
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) qs[u * D + off + e] = qv[u][e];
+      __syncthreads();
+    }
+  }
+  // B operand of S^T = K Q^T: lane (head n = lane % 16, k group lane / 16) holds q[n][32 ks + 8 (lane / 16) .. + 8],
+  // scaled, rounded to bf16 (as the chunk kernels round their pre-scaled queries); heads past G are zero
+  bf16x8 qb[NKS];
+  if (MM) {
+    const int n = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = n < G ? qs[n * D + ks * 32 + kg * 8 + e] : 0.f;
+      const uint4 pk = make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7]));
+      qb[ks] = __builtin_bit_cast(bf16x8, pk);
+    }
   }
   float o[G][VEC], mrun[G], lrun[G];
 #pragma unroll
@@ -131,28 +167,64 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
 
   constexpr int BLK = (DEC_THREADS / 64) * DEC_UN * KPW;   // rows per workgroup iteration
   for (int kb = k0; kb < k1; kb += BLK) {
-    V16 kf[DEC_UN], vf[DEC_UN];
+    V16 kf[MM ? 1 : DEC_UN], vf[DEC_UN];
     bool valid[DEC_UN];
+    bf16x8 ka[NSB][NKS];
+    if (MM) {
+      // A operand: lane (row lane % 16 of the 16-row block, k group lane / 16) fetches 16 bytes of that key's row
+      const bf16_t* Kh = (const bf16_t*)Kb;
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+        const int key = kb + wave * WROWS + sb * 16 + (lane & 15);
+        const bf16_t* kr = Kh + (int64_t)(key < k1 ? key : k0) * D + (lane >> 4) * 8;    // spare rows re-read the first row
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) ka[sb][ks] = *(const bf16x8*)(kr + ks * 32);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < DEC_UN; ++i) {
       const int key = kb + (wave * DEC_UN + i) * KPW + grp;
       valid[i] = key < k1;
       const int64_t row = (int64_t)(valid[i] ? key : k0) * D + off;   // spare slots re-read the first row
-      kf[i].raw = *(const raw_t*)(Kb + row);
+      if (!MM) kf[i].raw = *(const raw_t*)(Kb + row);
       vf[i].raw = *(const raw_t*)(Vb + row);
     }
     float s[DEC_UN][G];
+    if (MM) {
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      float* sl = slog + wave * (WROWS * G);
 #pragma unroll
-    for (int i = 0; i < DEC_UN; ++i)
+      for (int sb = 0; sb < NSB; ++sb) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int u = 0; u < G; ++u) {
-        float a = 0.f;
+        for (int ks = 0; ks < NKS; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[sb][ks], qb[ks], acc, 0, 0, 0);
+        // the lane holds rows 4 (lane / 16) + r of the block for head lane % 16
+        if ((lane & 15) < G)
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) a = fmaf(kf[i].get(e), qv[u][e], a);
-#pragma unroll
-        for (int x = 1; x < LPRP; x <<= 1) a += __shfl_xor(a, x, 64);
-        s[i][u] = valid[i] ? a : -INFINITY;
+          for (int r = 0; r < 4; ++r) sl[(sb * 16 + 4 * (lane >> 4) + r) * G + (lane & 15)] = acc[r];
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int i = 0; i < DEC_UN; ++i)
+#pragma unroll
+        for (int u = 0; u < G; ++u) s[i][u] = valid[i] ? sl[(i * KPW + grp) * G + u] : -INFINITY;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();                  // the next iteration rewrites the tile
+    } else {
+#pragma unroll
+      for (int i = 0; i < DEC_UN; ++i)
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          float a = 0.f;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a = fmaf(kf[0 + (MM ? 0 : i)].get(e), qv[u][e], a);
+#pragma unroll
+          for (int x = 1; x < LPRP; x <<= 1) a += __shfl_xor(a, x, 64);
+          s[i][u] = valid[i] ? a : -INFINITY;
+        }
+    }
     // one max decision per head for the UN rows of this lane group
     float muse[G];
     bool up_any = false;
