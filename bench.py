@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-head-budgets", action="store_true",
                     help="skip the head-wise-budget leg (profiling runs: keeps the launch counts those of the chunk step)")
+    ap.add_argument("--no-quant", action="store_true", help="skip the 4-bit-cache-rows leg")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain elementwise pass over 256 MiB (read 256 MiB, write 256 MiB): the "
                          "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -315,25 +316,27 @@ def main():
 
     # ---- head-wise budgets (one budget per KV head): the same layer with a pyramid of budgets of the
     # same total, steady state (every head at its budget), against equal budgets measured the same way
+    import dataclasses
+
+    def steady_ms(lay, n_fill, n_timed=20):
+        qc, kc, vc = chunks[min(1, need - 1)]
+        for _ in range(n_fill):
+            B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        s0.record()
+        for _ in range(n_timed):
+            B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
+        s1.record()
+        torch.cuda.synchronize()
+        return s0.elapsed_time(s1) / n_timed
+
     if w.h_kv >= 2 and w.h_kv <= B.LOCRET_MAX_HEAD_BUDGETS and not args.no_head_budgets:
-        def steady_ms(lay, n_fill, n_timed=20):
-            qc, kc, vc = chunks[min(1, need - 1)]
-            for _ in range(n_fill):
-                B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
-            s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            s0.record()
-            for _ in range(n_timed):
-                B.locret_prefill_chunk(lay.ctx, qc, kc, vc, qc.shape[0], w.n_s, 1, None, out, scores, None)
-            s1.record()
-            torch.cuda.synchronize()
-            return s0.elapsed_time(s1) / n_timed
         B.locret_reset(layer.ctx)                               # the decode steps above left it over its budget
         equal_ms = steady_ms(layer, (w.b + w.B - 1) // w.B + 4)
         lo_b = max(w.n_s, w.b // 4)
         pyr = [int(round(lo_b + (2 * w.b - 2 * lo_b) * (w.h_kv - 1 - m) / (w.h_kv - 1))) for m in range(w.h_kv)]
         pyr[-1] += w.h_kv * w.b - sum(pyr)                      # exactly the same total
-        import dataclasses
         lay2 = B.LocretLayer(B.config_from_workload(dataclasses.replace(w, b=max(pyr))), dev)
         lay2.set_weights(torch.from_numpy(W1h).to(dev).to(td), torch.from_numpy(W2h).to(dev).to(td))
         lay2.set_head_budgets(pyr)
@@ -343,6 +346,44 @@ def main():
         extra["head_budgets"] = {"budgets": pyr, "steady_ms_per_step": round(pyr_ms, 4),
                                  "equal_budgets_steady_ms_per_step": round(equal_ms, 4),
                                  "tokens_per_s": round(w.B / (pyr_ms * 1e-3), 1)}
+
+    # ---- 4-bit cache rows (the appendix's combination with KV-cache quantization): the same layer with
+    # kv_bits = 4, steady state; stage figures are pure kernel durations (profile mode 2)
+    if w.dtype == "bf16" and w.d in (64, 96, 128) and not args.no_quant:
+        wq = dataclasses.replace(w, kv_bits=4)
+        cfgq = B.config_from_workload(wq)
+        layq = B.LocretLayer(cfgq, dev)
+        layq.set_weights(torch.from_numpy(W1h).to(dev).to(td), torch.from_numpy(W2h).to(dev).to(td))
+        q_ms = steady_ms(layq, (w.b + w.B - 1) // w.B + 4)
+        B.locret_profile_mode(layq.ctx, 2)
+        B.locret_profile_enable(layq.ctx, 20)
+        steady_ms(layq, 0)
+        qst, nq = B.locret_profile_read(layq.ctx)
+        B.locret_profile_enable(layq.ctx, 0)
+        for _ in range(8):
+            B.locret_decode_step(layq.ctx, q1, k1, v1, 0, o1, None)
+        dq0, dq1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        dq0.record()
+        for _ in range(n_dec):
+            B.locret_decode_step(layq.ctx, q1, k1, v1, 0, o1, None)
+        dq1.record()
+        torch.cuda.synchronize()
+        layq.close()
+        rowb = w.d // 2 + 4 * (w.d // 32)
+        # per unit: packed K, V rows read and written, staging K, V rows written, score + position read and written, index read
+        cq_bytes = w.h_kv * w.b * (4 * rowb + 2 * w.d * 2 + 16 + 4)
+        cq_ms = qst[4] / max(1, nq)
+        extra["quantized_rows"] = {
+            "kv_bits": 4, "row_bytes": rowb, "steady_ms_per_step": round(q_ms, 4),
+            "tokens_per_s": round(w.B / (q_ms * 1e-3), 1),
+            "stage_ms_per_step": {k: round(v / max(1, nq), 4) for k, v in zip(B.PROF_STAGE_NAMES, qst)},
+            "compact": {"algorithmic_bytes": cq_bytes, "achieved": round(cq_bytes / (cq_ms * 1e-3) / 1e9, 1) if cq_ms > 0 else None,
+                        "unit": "GB/s", "frac": round(cq_bytes / (cq_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if cq_ms > 0 else None,
+                        "bytes_vs_bf16_rows": round(cq_bytes / (w.h_kv * w.b * (5 * w.d * 2 + 16 + 4)), 3)},
+            "decode_ms_per_token": round(dq0.elapsed_time(dq1) / n_dec, 4),
+            "workspace_bytes": B.locret_workspace_bytes(cfgq), "workspace_bytes_bf16_rows": B.locret_workspace_bytes(B.config_from_workload(w)),
+        }
 
     cpu = None
     if not args.no_cpu_baseline:

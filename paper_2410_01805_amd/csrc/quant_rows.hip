@@ -11,105 +11,230 @@
 // array per operand: the dequantized value lo + code * s of every row, K rotated to its slot's position.  It is a
 // pure function of the live packed copy: append and compaction write both, so a step still touches each row once.
 //
-// One wavefront per row: lane l owns dims 2l and 2l+1 (one byte of codes); the 16 lanes of a group find its
-// minimum and maximum with four butterfly steps.
+// Both kernels move 16 bytes per lane: a row is shared by head_dim/16 lanes, each owning two pieces of 8 dims that
+// are rotary partners, and a thread serves several KV heads so that the rotary-table entries of a position are
+// read once.
 #include "device_util.h"
 #include "kernels.h"
 
 namespace locret {
 
+
 __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
 
-// rotate this lane's two dims of a row held as (x0, x1) per lane, D/2 lanes per row, to position `pos`
+typedef unsigned int q4_u32x4 __attribute__((ext_vector_type(4)));
+
+// A row of D bf16 values is shared by NP = D/16 lanes (a power-of-two block of NPP lanes is reserved for it); lane p
+// owns two pieces of 8 dims, [8p, 8p+8) and [D/2 + 8p, D/2 + 8p + 8): eight rotary pairs (i, i + D/2).  Piece ids
+// run 0 .. 2 NP - 1 in dim order (piece q = dims [8q, 8q+8)); a quantization group is four consecutive pieces.
 template <int D>
-__device__ __forceinline__ void rotate_lane_pair(float& x0, float& x1, int lane, const float2* __restrict__ tab, int pos) {
-  const int half_lanes = D / 4;                                 // lanes that hold the low half of the row
-  const bool low = lane < half_lanes;
-  const int partner = low ? lane + half_lanes : lane - half_lanes;
-  const float p0 = __shfl(x0, partner & 63, 64), p1 = __shfl(x1, partner & 63, 64);
-  if (lane < D / 2) {
-    const int i = 2 * (low ? lane : lane - half_lanes);
-    const float2 c0 = tab[(int64_t)pos * (D / 2) + i], c1 = tab[(int64_t)pos * (D / 2) + i + 1];
-    // low half: a cos - b sin with b the partner; high half: b cos + a sin with a the partner
-    x0 = low ? x0 * c0.x - p0 * c0.y : x0 * c0.x + p0 * c0.y;
-    x1 = low ? x1 * c1.x - p1 * c1.y : x1 * c1.x + p1 * c1.y;
+struct Q4Lanes {
+  static constexpr int NP = D / 16;
+  static constexpr int NPP = NP <= 4 ? 4 : 8;
+};
+
+// min and max of the group that piece `piece` belongs to, gathered from the lanes of the row (lane block starts at
+// lane `base`): every lane offers the (min, max) of its two pieces.
+template <int D>
+__device__ __forceinline__ void group_min_max(int piece, int base, float mn0, float mx0, float mn1, float mx1, float& lo, float& hi) {
+  constexpr int NP = Q4Lanes<D>::NP;
+  const int g = piece >> 2;
+  lo = INFINITY;
+  hi = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int q = 4 * g + j;                      // a member piece: slot q / NP of lane q % NP
+    const int src = base + q % NP;
+    const float a0 = __shfl(mn0, src, 64), a1 = __shfl(mn1, src, 64);
+    const float b0 = __shfl(mx0, src, 64), b1 = __shfl(mx1, src, 64);
+    lo = fminf(lo, q / NP ? a1 : a0);
+    hi = fmaxf(hi, q / NP ? b1 : b0);
   }
 }
 
+// codes of 8 values against (lo, s); returns the packed dword (dim e in nibble e) and leaves the dequantized values
+__device__ __forceinline__ uint32_t quant8(float (&x)[8], float lo, float s) {
+  uint32_t w = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float c = fminf(fmaxf(rintf(__fdiv_rn(x[e] - lo, s)), 0.f), 15.f);
+    w |= (uint32_t)c << (4 * e);
+    x[e] = fmaf(c, s, lo);
+  }
+  return w;
+}
+
+__device__ __forceinline__ void unpack8_bf16(q4_u32x4 v, float (&x)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = bf2f((bf16_t)(v[i] & 0xffffu));
+    x[2 * i + 1] = bf2f((bf16_t)(v[i] >> 16));
+  }
+}
+__device__ __forceinline__ q4_u32x4 pack8_bf16(const float (&x)[8]) {
+  q4_u32x4 r = {pack2_bf16(x[0], x[1]), pack2_bf16(x[2], x[3]), pack2_bf16(x[4], x[5]), pack2_bf16(x[6], x[7])};
+  return r;
+}
+
+// Append: thread (t, p) quantizes its two pieces of the K row and of the V row of token t for the KV heads of its
+// block, writes the code dwords and (first lane of every group) the group's (scale, minimum), and the staging
+// values: what the row now stands for, K rotated to position n_c + t.
 template <int D>
 __global__ __launch_bounds__(256) void append_q4_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                         int Tn, int n_c, int seen, int h_kv, int cap,
                                                         uint8_t* __restrict__ Kq, uint8_t* __restrict__ Vq, int qstride,
                                                         bf16_t* __restrict__ Kst, bf16_t* __restrict__ Vst,
                                                         int32_t* __restrict__ P, const float2* __restrict__ tab,
-                                                        float* __restrict__ S_unscored) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-  if (row >= (int64_t)Tn * 2 * h_kv) return;                    // whole wavefronts leave together
-  const int t = (int)(row / (2 * h_kv)), r = (int)(row % (2 * h_kv));
-  const bool is_k = r < h_kv;
-  const int m = is_k ? r : r - h_kv;
-  const bool act = lane < D / 2;
-  const bf16_t* src = (is_k ? k : v) + ((int64_t)t * h_kv + m) * D;
-  const uint32_t two = act ? *(const uint32_t*)(src + 2 * lane) : 0u;
-  const float x0 = bf2f((bf16_t)(two & 0xffffu)), x1 = bf2f((bf16_t)(two >> 16));
-  float lo = fminf(x0, x1), hi = fmaxf(x0, x1);
+                                                        float* __restrict__ S_unscored, int hpb) {
+  constexpr int NP = Q4Lanes<D>::NP, NPP = Q4Lanes<D>::NPP;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int t_raw = (int)(gid / NPP), p_raw = (int)(gid % NPP);
+  // threads past the chunk and the spare lanes of a block stay in the shuffles (on clamped indices), write nothing
+  const bool act = t_raw < Tn && p_raw < NP;
+  const int t = min(t_raw, Tn - 1), p = min(p_raw, NP - 1);
+  const int base = (threadIdx.x & 63) - p_raw;                  // first lane of the row's block
+  float2 cs[8];
+  if (tab != nullptr) {
+    const float2* tr = tab + (int64_t)(n_c + t) * (D / 2) + 8 * p;
 #pragma unroll
-  for (int o = 1; o < 16; o <<= 1) {
-    lo = fminf(lo, __shfl_xor(lo, o, 64));
-    hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+    for (int e = 0; e < 8; ++e) cs[e] = tr[e];
   }
-  float s = bf2f(f2bf(__fdiv_rn(hi - lo, 15.0f)));
-  s = s > 0.f ? s : 1.0f;
-  const float c0 = fminf(fmaxf(rintf(__fdiv_rn(x0 - lo, s)), 0.f), 15.f);
-  const float c1 = fminf(fmaxf(rintf(__fdiv_rn(x1 - lo, s)), 0.f), 15.f);
-  uint32_t byte = (uint32_t)c0 | ((uint32_t)c1 << 4);
-  // four lanes' bytes into one dword, stored by the first of them
-  uint32_t w = byte | (__shfl_down(byte, 1, 64) << 8) | (__shfl_down(byte, 2, 64) << 16) | (__shfl_down(byte, 3, 64) << 24);
-  const int64_t slot = (int64_t)m * cap + n_c + t;
-  uint8_t* qrow = (is_k ? Kq : Vq) + slot * qstride;
-  if (act && (lane & 3) == 0) *(uint32_t*)(qrow + lane) = w;
-  if (act && (lane & 15) == 0) *(uint32_t*)(qrow + D / 2 + 4 * (lane >> 4)) = (uint32_t)f2bf(s) | ((uint32_t)f2bf(lo) << 16);
-  // staging: the values the row now stands for
-  float y0 = fmaf(c0, s, lo), y1 = fmaf(c1, s, lo);
-  if (is_k && tab != nullptr) rotate_lane_pair<D>(y0, y1, lane, tab, n_c + t);
-  if (act) *(uint32_t*)((is_k ? Kst : Vst) + slot * D + 2 * lane) = pack2_bf16(y0, y1);
-  if (is_k && lane == 0) {
-    P[slot] = seen + t;
-    if (S_unscored) S_unscored[slot] = __uint_as_float(0x7fc00000u);   // NaN: ranks last
+  const int m_lo = blockIdx.y * hpb, m_hi = min(h_kv, m_lo + hpb);
+  for (int m = m_lo; m < m_hi; ++m) {
+    const int64_t slot = (int64_t)m * cap + n_c + t;
+#pragma unroll
+    for (int kv = 0; kv < 2; ++kv) {
+      const bf16_t* src = (kv == 0 ? k : v) + ((int64_t)t * h_kv + m) * D;
+      float a[8], b[8];
+      unpack8_bf16(*(const q4_u32x4*)(src + 8 * p), a);
+      unpack8_bf16(*(const q4_u32x4*)(src + D / 2 + 8 * p), b);
+      float mn0 = a[0], mx0 = a[0], mn1 = b[0], mx1 = b[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) {
+        mn0 = fminf(mn0, a[e]); mx0 = fmaxf(mx0, a[e]);
+        mn1 = fminf(mn1, b[e]); mx1 = fmaxf(mx1, b[e]);
+      }
+      float lo0, hi0, lo1, hi1;
+      group_min_max<D>(p, base, mn0, mx0, mn1, mx1, lo0, hi0);
+      group_min_max<D>(NP + p, base, mn0, mx0, mn1, mx1, lo1, hi1);
+      float s0 = bf2f(f2bf(__fdiv_rn(hi0 - lo0, 15.0f))), s1 = bf2f(f2bf(__fdiv_rn(hi1 - lo1, 15.0f)));
+      s0 = s0 > 0.f ? s0 : 1.0f;
+      s1 = s1 > 0.f ? s1 : 1.0f;
+      const uint32_t w0 = quant8(a, lo0, s0), w1 = quant8(b, lo1, s1);     // a, b now hold the dequantized values
+      if (kv == 0 && tab != nullptr) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float lo = a[e] * cs[e].x - b[e] * cs[e].y, hi = b[e] * cs[e].x + a[e] * cs[e].y;
+          a[e] = lo;
+          b[e] = hi;
+        }
+      }
+      if (act) {
+        uint8_t* qrow = (kv == 0 ? Kq : Vq) + slot * qstride;
+        *(uint32_t*)(qrow + 4 * p) = w0;
+        *(uint32_t*)(qrow + D / 4 + 4 * p) = w1;
+        if ((p & 3) == 0) *(uint32_t*)(qrow + D / 2 + 4 * (p >> 2)) = (uint32_t)f2bf(s0) | ((uint32_t)f2bf(lo0) << 16);
+        if (((NP + p) & 3) == 0) *(uint32_t*)(qrow + D / 2 + 4 * ((NP + p) >> 2)) = (uint32_t)f2bf(s1) | ((uint32_t)f2bf(lo1) << 16);
+        bf16_t* st = (kv == 0 ? Kst : Vst) + slot * D;
+        *(q4_u32x4*)(st + 8 * p) = pack8_bf16(a);
+        *(q4_u32x4*)(st + D / 2 + 8 * p) = pack8_bf16(b);
+      }
+    }
+    if (act && p == 0) {
+      P[slot] = seen + t;
+      if (S_unscored) S_unscored[slot] = __uint_as_float(0x7fc00000u);   // NaN: ranks last
+    }
   }
 }
 
-// dst packed rows r = src packed rows kept[m][r]; staging rows r = their values, K rotated to position r.
-template <int D>
+// Compaction of packed rows: dst packed rows r = src packed rows kept[m][r]; staging rows r = their values, K rotated
+// to position r.  A thread owns slot r and the dims [8p, 8p+8) and [D/2 + 8p, D/2 + 8p + 8) of it, i.e. eight rotary
+// pairs, for ALL KV heads of its block (HB heads per batch of loads): the rotary-table entries of slot r are read
+// once, the staging stores are 16 bytes per lane, and the first row_stride/16 lanes of a row also move the packed
+// row itself, 16 bytes each.
+__device__ __forceinline__ void dequant8(uint32_t codes, uint32_t par, float (&x)[8]) {
+  const float s = bf2f((bf16_t)(par & 0xffffu)), lo = bf2f((bf16_t)(par >> 16));
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = fmaf((float)((codes >> (4 * e)) & 15u), s, lo);
+}
+
+template <int D, int HB>
 __global__ __launch_bounds__(256) void compact_q4_kernel(const uint8_t* __restrict__ Kqs, const uint8_t* __restrict__ Vqs,
                                                          const float* __restrict__ Ss, const int32_t* __restrict__ Ps,
                                                          uint8_t* __restrict__ Kqd, uint8_t* __restrict__ Vqd,
                                                          float* __restrict__ Sd, int32_t* __restrict__ Pd,
                                                          bf16_t* __restrict__ Kst, bf16_t* __restrict__ Vst,
                                                          const int32_t* __restrict__ kept, int kept_stride, int n_keep,
-                                                         int h_kv, int cap, int qstride, const float2* __restrict__ tab) {
-  const int lane = threadIdx.x & 63;
-  const int64_t id = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-  if (id >= (int64_t)2 * h_kv * n_keep) return;
-  const int r = (int)(id % n_keep);
-  const int mk = (int)(id / n_keep);                            // consecutive wavefronts: consecutive slots of one array
-  const int m = mk >> 1;
-  const bool is_k = (mk & 1) == 0;
-  const int src = kept[(int64_t)m * kept_stride + r];
-  const int64_t srow = (int64_t)m * cap + src, drow = (int64_t)m * cap + r;
-  const int ndw = qstride / 4;
-  const uint32_t w = lane < ndw ? *(const uint32_t*)((is_k ? Kqs : Vqs) + srow * qstride + 4 * lane) : 0u;
-  if (lane < ndw) *(uint32_t*)((is_k ? Kqd : Vqd) + drow * qstride + 4 * lane) = w;
-  const uint32_t byte = (__shfl(w, lane >> 2, 64) >> ((lane & 3) * 8)) & 0xffu;
-  const uint32_t par = __shfl(w, (D / 8 + (lane >> 4)) & 63, 64);
-  const float s = bf2f((bf16_t)(par & 0xffffu)), lo = bf2f((bf16_t)(par >> 16));
-  float y0 = fmaf((float)(byte & 15u), s, lo), y1 = fmaf((float)(byte >> 4), s, lo);
-  if (is_k && tab != nullptr) rotate_lane_pair<D>(y0, y1, lane, tab, r);
-  if (lane < D / 2) *(uint32_t*)((is_k ? Kst : Vst) + drow * D + 2 * lane) = pack2_bf16(y0, y1);
-  if (is_k && lane == 0) {
-    Sd[drow] = Ss[srow];
-    Pd[drow] = Ps[srow];
+                                                         int h_kv, int cap, int qstride, const float2* __restrict__ tab,
+                                                         int hpb) {
+  constexpr int NP = D / 16;                                    // lanes per row
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int r = (int)(gid / NP), p = (int)(gid % NP);
+  if (r >= n_keep) return;
+  const int g0 = (8 * p) / 32, g1 = (D / 2 + 8 * p) / 32;       // quantization groups of the lane's two pieces
+  const bool mover = p < qstride / 16;                          // also moves 16 bytes of every packed row
+  float2 cs[8];
+  if (tab != nullptr) {
+    const float2* tr = tab + (int64_t)r * (D / 2) + 8 * p;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[e] = tr[e];
+  }
+  const int m_lo = blockIdx.y * hpb, m_hi = min(h_kv, m_lo + hpb);
+  for (int m0 = m_lo; m0 < m_hi; m0 += HB) {
+    int src[HB];
+    uint32_t kc0[HB], kc1[HB], kp0[HB], kp1[HB], vc0[HB], vc1[HB], vp0[HB], vp1[HB];
+    q4_u32x4 kmv[HB], vmv[HB];
+#pragma unroll
+    for (int u = 0; u < HB; ++u) src[u] = kept[(int64_t)min(m0 + u, m_hi - 1) * kept_stride + r];   // spare iterations repeat the last head
+#pragma unroll
+    for (int u = 0; u < HB; ++u) {
+      const int m = min(m0 + u, m_hi - 1);
+      const uint8_t* kr = Kqs + ((int64_t)m * cap + src[u]) * qstride;
+      const uint8_t* vr = Vqs + ((int64_t)m * cap + src[u]) * qstride;
+      kc0[u] = *(const uint32_t*)(kr + 4 * p);
+      kc1[u] = *(const uint32_t*)(kr + D / 4 + 4 * p);
+      kp0[u] = *(const uint32_t*)(kr + D / 2 + 4 * g0);
+      kp1[u] = *(const uint32_t*)(kr + D / 2 + 4 * g1);
+      vc0[u] = *(const uint32_t*)(vr + 4 * p);
+      vc1[u] = *(const uint32_t*)(vr + D / 4 + 4 * p);
+      vp0[u] = *(const uint32_t*)(vr + D / 2 + 4 * g0);
+      vp1[u] = *(const uint32_t*)(vr + D / 2 + 4 * g1);
+      if (mover) {
+        kmv[u] = *(const q4_u32x4*)(kr + 16 * p);
+        vmv[u] = *(const q4_u32x4*)(vr + 16 * p);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < HB; ++u) {
+      const int m = m0 + u;
+      if (m >= m_hi) break;
+      const int64_t drow = (int64_t)m * cap + r;
+      if (mover) {
+        __builtin_nontemporal_store(kmv[u], (q4_u32x4*)(Kqd + drow * qstride + 16 * p));
+        __builtin_nontemporal_store(vmv[u], (q4_u32x4*)(Vqd + drow * qstride + 16 * p));
+      }
+      float a[8], bq[8];
+      dequant8(kc0[u], kp0[u], a);
+      dequant8(kc1[u], kp1[u], bq);
+      if (tab != nullptr) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float lo = a[e] * cs[e].x - bq[e] * cs[e].y, hi = bq[e] * cs[e].x + a[e] * cs[e].y;
+          a[e] = lo;
+          bq[e] = hi;
+        }
+      }
+      __builtin_nontemporal_store(pack8_bf16(a), (q4_u32x4*)(Kst + drow * D + 8 * p));
+      __builtin_nontemporal_store(pack8_bf16(bq), (q4_u32x4*)(Kst + drow * D + D / 2 + 8 * p));
+      dequant8(vc0[u], vp0[u], a);
+      dequant8(vc1[u], vp1[u], bq);
+      __builtin_nontemporal_store(pack8_bf16(a), (q4_u32x4*)(Vst + drow * D + 8 * p));
+      __builtin_nontemporal_store(pack8_bf16(bq), (q4_u32x4*)(Vst + drow * D + D / 2 + 8 * p));
+      if (p == 0) {
+        Sd[drow] = Ss[(int64_t)m * cap + src[u]];
+        Pd[drow] = Ps[(int64_t)m * cap + src[u]];
+      }
+    }
   }
 }
 
@@ -119,26 +244,34 @@ int q4_row_stride(int d) { return (q4_row_bytes(d) + 15) / 16 * 16; }
 
 void launch_append_q4(const Dims& D, const void* k, const void* v, int T, int n_c, int64_t seen, const CacheBuf& c,
                       const float2* tab, hipStream_t st, bool mark_unscored) {
-  const int64_t rows = (int64_t)T * 2 * D.h_kv;
-  const dim3 grid((unsigned)((rows + 3) / 4));
+  const int npp = D.d / 16 <= 4 ? 4 : 8;
+  const int64_t threads = (int64_t)T * npp;
+  const unsigned gx = (unsigned)((threads + 255) / 256);
+  int hpb = D.h_kv;
+  while (hpb > 1 && (int64_t)gx * ((D.h_kv + hpb - 1) / hpb) < 768) hpb = (hpb + 1) / 2;
+  const dim3 grid(gx, (unsigned)((D.h_kv + hpb - 1) / hpb));
   float* Su = mark_unscored ? c.S : nullptr;
 #define LOCRET_Q4A(DD)                                                                                              \
-  launch_kernel(append_q4_kernel<DD>, grid, dim3(256), 0, st, (const bf16_t*)k, (const bf16_t*)v, T, n_c,       \
-                     (int)seen, D.h_kv, D.cap, (uint8_t*)c.Kq, (uint8_t*)c.Vq, c.qstride, (bf16_t*)c.Kr, (bf16_t*)c.V, \
-                     c.P, D.rope ? tab : nullptr, Su)
+  launch_kernel(append_q4_kernel<DD>, grid, dim3(256), 0, st, (const bf16_t*)k, (const bf16_t*)v, T, n_c,            \
+                (int)seen, D.h_kv, D.cap, (uint8_t*)c.Kq, (uint8_t*)c.Vq, c.qstride, (bf16_t*)c.Kr, (bf16_t*)c.V,    \
+                c.P, D.rope ? tab : nullptr, Su, hpb)
   if (D.d == 128) LOCRET_Q4A(128); else if (D.d == 96) LOCRET_Q4A(96); else LOCRET_Q4A(64);
 #undef LOCRET_Q4A
 }
 
 void launch_compact_q4(const Dims& D, const CacheBuf& s, const CacheBuf& t, const int32_t* kept, int kept_stride,
                        int n_keep, const float2* tab, hipStream_t st) {
-  const int64_t rows = (int64_t)2 * D.h_kv * n_keep;
-  if (rows == 0) return;
-  const dim3 grid((unsigned)((rows + 3) / 4));
+  const int64_t threads = (int64_t)n_keep * (D.d / 16);
+  if (threads == 0) return;
+  // as in the bf16 compaction: a thread serves `hpb` KV heads, fewer when that leaves too few workgroups
+  const unsigned gx = (unsigned)((threads + 255) / 256);
+  int hpb = D.h_kv;
+  while (hpb > 2 && (int64_t)gx * ((D.h_kv + hpb - 1) / hpb) < 768) hpb = (hpb + 1) / 2;
+  const dim3 grid(gx, (unsigned)((D.h_kv + hpb - 1) / hpb));
 #define LOCRET_Q4C(DD)                                                                                              \
-  launch_kernel(compact_q4_kernel<DD>, grid, dim3(256), 0, st, (const uint8_t*)s.Kq, (const uint8_t*)s.Vq, s.S,  \
-                     s.P, (uint8_t*)t.Kq, (uint8_t*)t.Vq, t.S, t.P, (bf16_t*)t.Kr, (bf16_t*)t.V, kept, kept_stride,    \
-                     n_keep, D.h_kv, D.cap, s.qstride, D.rope ? tab : nullptr)
+  launch_kernel((compact_q4_kernel<DD, 2>), grid, dim3(256), 0, st, (const uint8_t*)s.Kq, (const uint8_t*)s.Vq, s.S,  \
+                s.P, (uint8_t*)t.Kq, (uint8_t*)t.Vq, t.S, t.P, (bf16_t*)t.Kr, (bf16_t*)t.V, kept, kept_stride,       \
+                n_keep, D.h_kv, D.cap, s.qstride, D.rope ? tab : nullptr, hpb)
   if (D.d == 128) LOCRET_Q4C(128); else if (D.d == 96) LOCRET_Q4C(96); else LOCRET_Q4C(64);
 #undef LOCRET_Q4C
 }

@@ -148,3 +148,33 @@ def test_4bit_rows_shrink_the_workspace():
     # two copies of K, V and the rotated shadow (1536 B per unit) against two packed copies of K, V (320 B) + one
     # bf16 staging pair (512 B)
     assert plain - quant >= rows * (1536 - 832) * 0.95
+
+
+def test_config3_shape_with_4bit_rows_reaches_steady_state():
+    """Config 3's layer and launch shapes (chunks of 4096, budget 16384) with 4-bit rows, 6 chunks: two steady-state
+    steps.  Kept indices bit-exact on every chunk (teacher-forced), the library's scores on every chunk, attention on
+    sampled rows, and at the end every packed row of the cache bit for bit."""
+    import dataclasses
+    from concurrent.futures import ThreadPoolExecutor
+    from tests.gpu_util import kappa_for
+    w = dataclasses.replace(synth.WORKLOADS["cfg3_llama_128k"], kv_bits=4, N=6 * 4096)
+    layer, W1, W2 = make_layer(w)
+    o = _oracle(w, W1, W2)
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        chunks = list(ex.map(lambda c: synth.chunk(w, c), range(w.n_chunks)))
+    rng = np.random.default_rng(3)
+    for c, (q, k, v) in enumerate(chunks):
+        n_c, T = o.n_c, q.shape[0]
+        rows = np.sort(rng.choice(T, size=12, replace=False)) if c in (0, 4, 5) else None
+        out_ref = o.attention(q, k, v, rows=rows) if rows is not None else None
+        sc_ref = o.score(q, k, v)
+        kept_ref = o.evict_compact(sc_ref, k, v, w.n_s)
+        out, sc, kept = layer.prefill_chunk(dev(q, w), dev(k, w), dev(v, w), w.n_s, scores_in=torch.from_numpy(sc_ref).to(DEV))
+        tag = f"cfg3 shape, 4-bit rows, chunk {c}"
+        np.testing.assert_array_equal(kept.cpu().numpy()[:, :min(n_c + T, w.b)], kept_ref, err_msg=tag)
+        assert_close(sc.cpu().numpy(), sc_ref, w.dtype, tag + " scores")
+        if rows is not None:
+            assert_close(host(out[rows]), out_ref[rows], w.dtype, tag + " attention", per_row=True, kappa=kappa_for(w))
+    assert layer.cache_len == o.n_c == w.b
+    _assert_packed_cache_equal(layer, o, w, "cfg3 shape final cache")
+    layer.close()
