@@ -173,17 +173,20 @@ __device__ __forceinline__ void select_reg_body(const SelectArgs& a, int m, uint
     need_eq = remaining;
   }
 
-  // ordered compaction over the registers
-  uint32_t tot_gt = 0, tot_eq = 0;
+  // ---- ordered compaction over the registers ---------------------------------------------------------------
+  // totals per wavefront: kept-for-sure keys (> tau) by ballots, keys equal to tau counted per thread first
+  uint32_t tot_gt = 0, my_eq = 0;
 #pragma unroll
   for (int j = 0; j < MAXR; ++j) {
     tot_gt += __popcll(__ballot(j < nvalid && k[j] > tau));
-    tot_eq += __popcll(__ballot(j < nvalid && k[j] == tau));
+    my_eq += (j < nvalid && k[j] == tau) ? 1u : 0u;
   }
+  uint32_t tot_eq = my_eq;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) tot_eq += __shfl_xor(tot_eq, o, 64);
   if (lane == 0) { wsum[wave] = tot_gt; wsum[16 + wave] = tot_eq; }
   __syncthreads();
   uint32_t run_gt = sum_before<NWAVES>(wsum, wave), run_eq = sum_before<NWAVES>(wsum + 16, wave);
-  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   // kept list: pinned prefix [0, n_pin), then the chosen candidates, then the stabilizers
   int32_t* out = a.kept + (int64_t)m * a.kept_stride + n_pin;
   int32_t* out2 = a.kept2 ? a.kept2 + (int64_t)m * a.stride2 + n_pin : nullptr;
@@ -191,20 +194,38 @@ __device__ __forceinline__ void select_reg_body(const SelectArgs& a, int m, uint
     out[i - n_pin] = i;
     if (out2) out2[i - n_pin] = i;
   }
+  if (tot_eq == 0) {
+    // the common case, decided per wavefront: none of its keys equals tau, so a key is kept iff it is above tau and
+    // its place is the count of kept keys before it (the equal keys of earlier wavefronts add a constant)
+    uint32_t base = run_gt + min(run_eq, need_eq);
 #pragma unroll
-  for (int j = 0; j < MAXR; ++j) {
-    const bool gt = j < nvalid && k[j] > tau;
-    const bool eq = j < nvalid && k[j] == tau;
-    const uint64_t bg = __ballot(gt), be = __ballot(eq);
-    const uint32_t gt_before = run_gt + __popcll(bg & lt_mask);
-    const uint32_t eq_before = run_eq + __popcll(be & lt_mask);
-    if (gt || (eq && eq_before < need_eq)) {
-      const uint32_t pos = gt_before + min(eq_before, need_eq);
-      out[pos] = n_pin + first + j * 64;
-      if (out2) out2[pos] = n_pin + first + j * 64;
+    for (int j = 0; j < MAXR; ++j) {
+      const bool gt = j < nvalid && k[j] > tau;
+      const uint64_t bg = __ballot(gt);
+      if (gt) {
+        const uint32_t pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+        out[pos] = n_pin + first + j * 64;
+        if (out2) out2[pos] = n_pin + first + j * 64;
+      }
+      base += __popcll(bg);
     }
-    run_gt += __popcll(bg);
-    run_eq += __popcll(be);
+  } else {
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int j = 0; j < MAXR; ++j) {
+      const bool gt = j < nvalid && k[j] > tau;
+      const bool eq = j < nvalid && k[j] == tau;
+      const uint64_t bg = __ballot(gt), be = __ballot(eq);
+      const uint32_t gt_before = run_gt + __popcll(bg & lt_mask);
+      const uint32_t eq_before = run_eq + __popcll(be & lt_mask);
+      if (gt || (eq && eq_before < need_eq)) {
+        const uint32_t pos = gt_before + min(eq_before, need_eq);
+        out[pos] = n_pin + first + j * 64;
+        if (out2) out2[pos] = n_pin + first + j * 64;
+      }
+      run_gt += __popcll(bg);
+      run_eq += __popcll(be);
+    }
   }
   for (int i = n_cand + tid; i < L - n_pin; i += NT) {
     out[kk + (i - n_cand)] = n_pin + i;
