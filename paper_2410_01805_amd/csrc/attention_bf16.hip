@@ -21,7 +21,7 @@
 // Softmax as in attention_pp.hip: queries pre-scaled by scale * log2(e) (and rotated here when the
 // rotary table is passed), S chains started from -(running max), exp2 / bf16 pack / two-way dot
 // products per tile, the running max moved only on the first tile and when a lane's probability
-// sum reaches 2^8.
+// sum reaches 2^30.
 //
 // K tile in LDS: [64 keys][D + 8]; V^T tile in LDS: [D][64 + 8], transposed on the way in by 4x8
 // register blocks.  The 16-byte row pad makes the stride an odd number of 16-byte chunks, so the
@@ -307,10 +307,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void attn_mfma_kernel(const bf16_t* _
       };
       exp_pack_sum();
       // The running max moves only on the first tile and when some lane's sum over its 32 keys reaches
-      // 2^RESCALE_LOG2 (any probability that large, an overflow included, shows there): then take the
+      // RESCALE_SUM = 2^30 (any probability that large, an overflow included, shows there): then take the
       // row max, raise the running max by it, scale sum and accumulator, refresh negm, correct this
       // tile's logits (formed against the old max) and redo its probabilities.
-      if (fresh || __any(!(ps < 256.f))) {
+      if (fresh || __any(!(ps < RESCALE_SUM))) {
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -431,13 +431,15 @@ bool attention_bf16_attaches_timer(const Dims& Dm) { return Dm.d == 64 || Dm.d =
 bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope; }
 
 bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
-  return Dm.bf16 && Dm.tune.fuse_select && pp_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
+  return Dm.bf16 && Dm.tune.fuse_select && !Dm.tune.attn_q2 && pp_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
 }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel,
                            const HeadLens* n_c_h, float* split_part, size_t split_floats) {
   const HeadLens hl = head_lens_or_common(n_c_h);
+  if (Dm.tune.attn_q2 && pp_applies(Dm) && !hl.ragged && sel == nullptr &&
+      launch_attention_bf16_q2(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (pp_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h, split_part, split_floats)) return;
 #define LOCRET_CASE(DD)                                                                        \
   case DD:                                                                                     \

@@ -11,7 +11,7 @@
 // Tiles past the end are fetched through a zero-length buffer descriptor (they arrive as zeros).
 // Softmax: every S chain starts from an accumulator holding -(running max), so the MFMA result is the exponent;
 // the running max is set by the first tile and raised only when a lane's probability sum over its 32 keys
-// reaches 2^8 (which also catches any overflow).
+// reaches 2^30 (which also catches any overflow).
 //
 // A wavefront's tile is a chain S (16 MFMAs) -> softmax (32 exp2 on the transcendental unit, ~640
 // cycles) -> PV (16 MFMAs).  Left alone, the two wavefronts of a SIMD drift into the same phase:
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(PP_NW * 64, 2) void attn_pp_kernel(const bf16_t* __
         ps = ps0 + ps1;
       };
       exp_pack_sum();
-      if (fresh || __any(!(ps < 256.f))) {     // rare: set or raise the running max
+      if (fresh || __any(!(ps < RESCALE_SUM))) {     // rare: set or raise the running max
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)

@@ -12,6 +12,13 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int KT = 64;   // keys per tile
 constexpr float RESCALE_LOG2 = 8.f;
+// The matrix-core kernels raise a query's running max only when its probability sum over one key tile reaches this
+// (2^30): probabilities are formed against a max that may be up to 30 binary orders too low, which float32
+// accumulators and bf16 probabilities (same exponent range) hold with room to spare (2^30 * 2^15 keys * |v| << 2^127),
+// and which any overflow also trips.  At 2^8 the path was taken in a quarter of the tiles of a workload whose
+// large logits arrive late (keys planted 4x larger), each time rescaling the accumulators and redoing the tile's
+// exponentials.
+constexpr float RESCALE_SUM = 1073741824.f;
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 x = {a, b};
