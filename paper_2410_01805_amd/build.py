@@ -28,7 +28,6 @@ FLAGS = [
 # is fixed instead of left to what precedes the loops.
 FILE_FLAGS = {
     "attention_pp.hip": ["-mllvm", "-align-all-nofallthru-blocks=8"],
-    "attention_q2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

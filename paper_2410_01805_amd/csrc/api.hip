@@ -62,7 +62,6 @@ Tuning tuning_from_env() {
   Tuning t;
   const char* v = getenv("LOCRET_ATTN_VARIANT");
   t.attn_regstaged = v && !strcmp(v, "regstaged");
-  t.attn_q2 = v && !strcmp(v, "q2");
   t.pp_split = env_int("LOCRET_PP_SPLIT", -1);
   t.pp_spread = env_int("LOCRET_PP_SPREAD", -1);
   t.score_split = env_int("LOCRET_SCORE_SPLIT", -1);

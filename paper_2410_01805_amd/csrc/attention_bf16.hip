@@ -431,15 +431,13 @@ bool attention_bf16_attaches_timer(const Dims& Dm) { return Dm.d == 64 || Dm.d =
 bool attention_bf16_rotates_q(const Dims& Dm) { return Dm.rope; }
 
 bool attention_bf16_fuses_select(const Dims& Dm, int n_cand) {
-  return Dm.bf16 && Dm.tune.fuse_select && !Dm.tune.attn_q2 && pp_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
+  return Dm.bf16 && Dm.tune.fuse_select && pp_applies(Dm) && attention_pp_fuses_select(Dm, n_cand);
 }
 
 void launch_attention_bf16(const Dims& Dm, const void* q, const void* Kx, const void* V, void* out, int T, int n_c,
                            float scale, hipStream_t st, const float2* q_rot_tab, LaunchTimer tm, const SelectArgs* sel,
                            const HeadLens* n_c_h, float* split_part, size_t split_floats) {
   const HeadLens hl = head_lens_or_common(n_c_h);
-  if (Dm.tune.attn_q2 && pp_applies(Dm) && !hl.ragged && sel == nullptr &&
-      launch_attention_bf16_q2(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st)) return;
   if (pp_applies(Dm) && launch_attention_bf16_pp(Dm, tm, q, q_rot_tab, Kx, V, out, T, n_c, scale, st, sel, n_c_h, split_part, split_floats)) return;
 #define LOCRET_CASE(DD)                                                                        \
   case DD:                                                                                     \

@@ -98,7 +98,6 @@ struct SelectArgs {
 // LOCRET_FUSE_SELECT), and carried with the context's dimensions; no launch path reads the environment.
 struct Tuning {
   int attn_regstaged = 0;   // 1: the register-staged attention kernel also where the direct-to-LDS one applies
-  int attn_q2 = 0;          // 1: the 64-queries-per-wavefront direct-to-LDS kernel where it applies (head_dim 128)
   int pp_split = -1;        // key ranges per item of the direct-to-LDS attention kernel: -1 chosen per launch, 0 never, k always k
   int pp_spread = -1;       // its workgroup order: -1 by head lengths, 0 one KV head per XCD, 1 every head over all XCDs
   int score_split = -1;     // contraction slices of the retaining head: -1 chosen per launch, 0 never, k always k
@@ -172,9 +171,6 @@ bool launch_attention_bf16_pp(const Dims& D, LaunchTimer tm, const void* q, cons
                               const void* V, void* out, int T, int n_c, float scale, hipStream_t st,
                               const SelectArgs* sel = nullptr, const HeadLens* n_c_h = nullptr,
                               float* split_part = nullptr, size_t split_floats = 0);
-// The direct-to-LDS kernel with 64 queries per wavefront (attention_q2.hip; d = 128, equal head lengths).
-bool launch_attention_bf16_q2(const Dims& D, LaunchTimer tm, const void* q, const float2* tab, const void* Kx, const void* V, void* out,
-                              int T, int n_c, float scale, hipStream_t st);
 // Floats of scratch the direct-to-LDS attention kernel wants for launches that split the key range (short chunks);
 // 0 when the shape never splits.  Without the buffer it does not split.
 size_t attention_pp_split_floats(const Dims& D, int chunk_max);

@@ -129,15 +129,6 @@ def test_register_staged_attention_kernel_on_head_dims_128_and_96(kw, monkeypatc
     layer.close()
 
 
-@pytest.mark.parametrize("kw", [SMALL[4], SMALL[7]], ids=["bf16_llama_like", "bf16_ns_gt_B"])
-def test_64_queries_per_wavefront_attention_kernel(kw, monkeypatch):
-    # LOCRET_ATTN_VARIANT=q2: the direct-to-LDS kernel with four wavefronts of 64 queries (head_dim 128)
-    monkeypatch.setenv("LOCRET_ATTN_VARIANT", "q2")
-    w = synth.tiny(**kw)
-    layer, o, _ = _run_stream(w, teacher_forced=True)
-    layer.close()
-
-
 @pytest.mark.parametrize("n_split", ["2", "3", "8"])
 def test_key_split_of_the_head_dim_128_kernel_forced(n_split, monkeypatch):
     # LOCRET_PP_SPLIT=k (read when the context is created) cuts every (head group, token tile) item into k key ranges whose partial
