@@ -361,15 +361,34 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(const T* __res
 // fence was measured 3x slower than both kernels together (every workgroup then pays for making its
 // partials visible across the eight L2s), while a kernel boundary does that once.
 constexpr int DEC_MERGE_THREADS = 1024;
+constexpr int DEC_MERGE_PRE = 12;       // vector elements a thread requests before anything else
+constexpr int DEC_MERGE_WS = 2048;      // splits whose weights are kept in LDS
 template <typename T>
 __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const float* __restrict__ part, int n_splits,
                                                                          int d, T* __restrict__ out) {
+  // The kernel is a chain of memory latencies, not of bytes (45 KB per head): every load that does not depend on
+  // another is requested up front.  Thread (e, r) owns element e of splits r, r + R, ...; the first
+  // DEC_MERGE_PRE of them are in flight while the maxima and sums of the splits are reduced.
   __shared__ float red[2 * (DEC_MERGE_THREADS / 64)];
+  __shared__ float wsm[DEC_MERGE_WS];
+  __shared__ float acc_s[DEC_MERGE_THREADS];
   const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int pw = d + 2;
   const float* p = part + (int64_t)j * n_splits * pw;
-  float mx = -INFINITY;
-  for (int s = tid; s < n_splits; s += DEC_MERGE_THREADS) mx = fmaxf(mx, p[s * pw + d]);
+  constexpr int R = DEC_MERGE_THREADS / 128;   // d <= 128
+  const int e = tid % 128, r = tid / 128;
+  // (addresses are clamped instead of the loads being predicated: a conditional load is a branch, and the wait
+  // counters cannot be tracked across it, so every such load would be waited for before the next is issued)
+  float pv[DEC_MERGE_PRE];
+  const int ec = min(e, d - 1);
+#pragma unroll
+  for (int i = 0; i < DEC_MERGE_PRE; ++i) pv[i] = p[min(r + i * R, n_splits - 1) * pw + ec];
+  // max and sum of split tid in registers; further splits of this thread (more than 1024 splits) are read again
+  const float2 ml = *(const float2*)(p + min(tid, n_splits - 1) * pw + d);     // pw and d are even: 8-byte aligned
+  const float m0 = tid < n_splits ? ml.x : -INFINITY;
+  const float l0 = tid < n_splits ? ml.y : 0.f;
+  float mx = m0;
+  for (int s = tid + DEC_MERGE_THREADS; s < n_splits; s += DEC_MERGE_THREADS) mx = fmaxf(mx, p[s * pw + d]);
 #pragma unroll
   for (int x = 32; x >= 1; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x, 64));
   if (lane == 0) red[wave] = mx;
@@ -377,31 +396,39 @@ __global__ __launch_bounds__(DEC_MERGE_THREADS) void decode_merge_kernel(const f
   float M = red[0];
 #pragma unroll
   for (int i = 1; i < DEC_MERGE_THREADS / 64; ++i) M = fmaxf(M, red[i]);
+  // weights w_s = 2^(m_s - M) (a split without keys carries max -inf and weighs 0)
   float ls = 0.f;
-  for (int s = tid; s < n_splits; s += DEC_MERGE_THREADS)
-    ls = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + d + 1], ls);
+  {
+    const float w = __builtin_amdgcn_exp2f(m0 - M);
+    wsm[tid] = w;
+    ls = w * l0;
+    for (int s = tid + DEC_MERGE_THREADS; s < n_splits; s += DEC_MERGE_THREADS) {
+      const float w2 = __builtin_amdgcn_exp2f(p[s * pw + d] - M);
+      if (s < DEC_MERGE_WS) wsm[s] = w2;
+      ls = fmaf(w2, p[s * pw + d + 1], ls);
+    }
+  }
 #pragma unroll
   for (int x = 32; x >= 1; x >>= 1) ls += __shfl_xor(ls, x, 64);
   if (lane == 0) red[DEC_MERGE_THREADS / 64 + wave] = ls;
-  __syncthreads();
+  __syncthreads();                                   // also publishes the weights
   float l = 0.f;
 #pragma unroll
   for (int i = 0; i < DEC_MERGE_THREADS / 64; ++i) l += red[DEC_MERGE_THREADS / 64 + i];
   const float inv = 1.f / l;
-  // thread (e, r): element e, splits r, r + R, ...; the R partial sums of an element meet in LDS
-  __shared__ float acc_s[DEC_MERGE_THREADS];
-  constexpr int R = DEC_MERGE_THREADS / 128;   // d <= 128
-  const int e = tid % 128, r = tid / 128;
-  float a0 = 0.f, a1 = 0.f;
+  float a0 = 0.f;
   if (e < d) {
-    int s = r;
-    for (; s + R < n_splits; s += 2 * R) {     // two independent loads in flight
-      a0 = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a0);
-      a1 = fmaf(__builtin_amdgcn_exp2f(p[(s + R) * pw + d] - M), p[(s + R) * pw + e], a1);
+#pragma unroll
+    for (int i = 0; i < DEC_MERGE_PRE; ++i) {
+      const int s = r + i * R;
+      if (s < n_splits) a0 = fmaf(wsm[s], pv[i], a0);
     }
-    if (s < n_splits) a0 = fmaf(__builtin_amdgcn_exp2f(p[s * pw + d] - M), p[s * pw + e], a0);
+    for (int s = r + DEC_MERGE_PRE * R; s < n_splits; s += R) {
+      const float w = s < DEC_MERGE_WS ? wsm[s] : __builtin_amdgcn_exp2f(p[s * pw + d] - M);
+      a0 = fmaf(w, p[s * pw + e], a0);
+    }
   }
-  acc_s[tid] = a0 + a1;
+  acc_s[tid] = a0;
   __syncthreads();
   if (tid < d) {
     float t = 0.f;
