@@ -190,6 +190,19 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
   };
 
+  // The load wavefronts fetch the W2 rows of this hidden block (first 32 KV heads, zero beyond h_kv) before the
+  // pipeline starts and hold them until the epilogue: 16 registers they have to spare, and the epilogue does not
+  // begin with a trip to memory.  Element i = hidden unit i / 32, KV head i % 32.
+  float w2pre[16];
+  if (!KSPLIT && producer) {
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+      const int i = (tid - 256) + 256 * jj, hh = i >> 5, mm = i & 31;
+      const float x = W2f[(int64_t)(r0 + hh) * h_kv + min(mm, h_kv - 1)];     // address clamped, value masked: no branch
+      w2pre[jj] = mm < h_kv ? x : 0.f;
+    }
+  }
+
   // One barrier per stage.  Invariant at barrier s: stages up to s+1 are in LDS (a producer arrives once at
   // most one stage = 8 of its loads is still in flight) and every consumer has left stage s-1.  Behind it a
   // producer starts stage s+3 in the buffer of stage s-1; a consumer computes stage s and then requests the
@@ -260,28 +273,44 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   for (int m0 = 0; m0 < h_kv; m0 += 32) {
     const int mc = min(32, h_kv - m0);
     __syncthreads();                               // ring / previous chunk no longer read
-    for (int i = tid; i < RT_M * mc; i += 512) {
-      int hh = i / mc, mm = i % mc;
-      sm.ep.W2s[hh * 32 + mm] = W2f[(int64_t)(r0 + hh) * h_kv + m0 + mm];
+    if (m0 == 0 && producer) {
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) sm.ep.W2s[(tid - 256) + 256 * jj] = w2pre[jj];
+    } else if (m0 > 0) {
+      for (int i = tid; i < RT_M * 32; i += 512) {
+        const int hh = i >> 5, mm = i & 31;
+        sm.ep.W2s[i] = mm < mc ? W2f[(int64_t)(r0 + hh) * h_kv + m0 + mm] : 0.f;
+      }
     }
     __syncthreads();
-    for (int mm = 0; mm < mc && !producer; ++mm) {
-      float s0 = 0.f, s1 = 0.f;                    // token blocks b = 0, 1
+    // four KV heads at a time: one 16-byte read of the W2 row per accumulator element
+    for (int mq = 0; mq < mc && !producer; mq += 4) {
+      float sb[2][4];                              // [token block][KV head of the four]
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sb[b][i] = 0.f;
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          int hh = wm * 64 + a * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
-          float w = sm.ep.W2s[hh * 32 + mm];
-          s0 = fmaf(acc[a][0][r], w, s0);
-          s1 = fmaf(acc[a][1][r], w, s1);
+          const int hh = wm * 64 + a * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
+          const float4 w = *(const float4*)&sm.ep.W2s[hh * 32 + mq];
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            sb[b][0] = fmaf(acc[a][b][r], w.x, sb[b][0]);
+            sb[b][1] = fmaf(acc[a][b][r], w.y, sb[b][1]);
+            sb[b][2] = fmaf(acc[a][b][r], w.z, sb[b][2]);
+            sb[b][3] = fmaf(acc[a][b][r], w.w, sb[b][3]);
+          }
         }
-      s0 = sum_across_halves(s0);
-      s1 = sum_across_halves(s1);
-      if (hi == 0) {
-        sm.ep.red[(wm * RT_N + wn * 64 + n32) * 33 + mm] = s0;
-        sm.ep.red[(wm * RT_N + wn * 64 + 32 + n32) * 33 + mm] = s1;
-      }
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float v = sum_across_halves(sb[b][i]);
+          if (hi == 0) sm.ep.red[(wm * RT_N + wn * 64 + b * 32 + n32) * 33 + mq + i] = v;   // columns >= mc: zeros, not read
+        }
     }
     __syncthreads();
     for (int i = tid; i < RT_N * mc; i += 512) {
