@@ -144,7 +144,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     b_rd[ks] = RT_TILE_B + (wn * 64 + n32) * 128 + pos;
   }
 
-  // The fragments of contraction steps 0 and 1 of a stage are requested at the end of the stage before
+  // The fragments of contraction steps 0 and 1 of a stage are requested during the stage before
   // (its data is already in LDS then, see the invariant below), so the MFMAs start right behind the barrier.
   bf16x8 pre[8];
   auto prefetch = [&](int buf) {
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
       pre[ks * 4 + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
     }
   };
-  auto compute = [&](int buf) {
+  auto compute = [&](int buf, int next_buf) {
     const unsigned char* base = sm.ring + buf * RT_STAGE_B;
     bf16x8 af[4][2], bfr[4][2];
 #pragma unroll
@@ -181,13 +181,16 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][0], acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][1], acc[1][1], 0, 0, 0);
     }
-    // issue order: one of the 8 remaining fragment reads behind each of the first 8 MFMAs
+    // the first fragments of the next stage (in LDS already, see the invariant below): requested behind this stage's
+    // last MFMAs, so that they have arrived when the barrier opens (requested after the last MFMA, their latency
+    // of a few hundred cycles stood between every two stages: 724 cycles per stage for 512 cycles of MFMAs)
+    prefetch(next_buf);
+    // issue order: one of the 16 fragment reads behind each MFMA
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
   };
 
   // The load wavefronts fetch the W2 rows of this hidden block (first 32 KV heads, zero beyond h_kv) before the
@@ -232,11 +235,8 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
       for (int u = 0; u < RT_STAGES; ++u)
         if (s0 + u < n_stages) {
-          compute(u);
-          if (s0 + u + 1 < n_stages) {
-            prefetch((u + 1) % RT_STAGES);
-            asm volatile("s_barrier" ::: "memory");
-          }
+          compute(u, (u + 1) % RT_STAGES);     // (behind the last stage the prefetch reads a buffer nobody needs)
+          if (s0 + u + 1 < n_stages) asm volatile("s_barrier" ::: "memory");
         }
     }
   }
