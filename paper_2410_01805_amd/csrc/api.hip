@@ -64,6 +64,7 @@ Tuning tuning_from_env() {
   t.attn_regstaged = v && !strcmp(v, "regstaged");
   t.pp_split = env_int("LOCRET_PP_SPLIT", -1);
   t.pp_spread = env_int("LOCRET_PP_SPREAD", -1);
+  t.score_nt = env_int("LOCRET_SCORE_NT", 0);
   t.score_split = env_int("LOCRET_SCORE_SPLIT", -1);
   const int dk = env_int("LOCRET_DEC_KEYS", 0);
   t.dec_keys = (dk >= 64 && dk <= 65536 && dk % 64 == 0) ? dk : 0;

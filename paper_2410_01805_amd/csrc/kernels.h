@@ -99,6 +99,7 @@ struct SelectArgs {
 struct Tuning {
   int attn_regstaged = 0;   // 1: the register-staged attention kernel also where the direct-to-LDS one applies
   int pp_split = -1;        // key ranges per item of the direct-to-LDS attention kernel: -1 chosen per launch, 0 never, k always k
+  int score_nt = 0;         // retaining head: tokens per workgroup (0: by the chunk length, 64, 128)
   int pp_spread = -1;       // its workgroup order: -1 by head lengths, 0 one KV head per XCD, 1 every head over all XCDs
   int score_split = -1;     // contraction slices of the retaining head: -1 chosen per launch, 0 never, k always k
   int dec_keys = 0;         // keys per split of the decode step: 0 chosen per launch, else a multiple of 64 in 64..65536

@@ -61,7 +61,9 @@ __device__ __forceinline__ float sum_across_halves(float x) {
 // KSPLIT (short chunks, too few 128 x 128 tiles for the CUs): blockIdx.z takes a slice of the contraction and
 // the workgroup leaves its partial pre-activations zpart[z][t][r]; score_finish_kernel sums the slices and
 // applies SiLU and W2.  KSPLIT = false: the whole contraction, epilogue below.
-template <bool KSPLIT>
+// NT = tokens per workgroup: 128 (2 x 2 wavefronts of 64 hidden units x 64 tokens), or 64 (64 x 32 each) for chunks
+// that would leave half of the CUs without a 128-token tile; the hidden block stays 128 wide.
+template <bool KSPLIT, int NT>
 __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                          const bf16_t* __restrict__ v, int Tn, int hd, int kvd,
                                                          const bf16_t* __restrict__ W1t,
@@ -76,33 +78,37 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   const bool producer = wave >= 4;               // wave-uniform
   const int pw = wave & 3;                       // producer: fills rows pw*32 .. pw*32+31 of both tiles
   const int wm = (wave >> 1) & 1, wn = wave & 1; // consumer: 64 x 64 sub-tile
-  const int t0 = blockIdx.x * RT_N;
+  static_assert(NT == 128 || NT == 64, "token tile");
+  constexpr int NBT = NT / 64;                   // 32-token blocks per wavefront
+  constexpr int B_LOADS = NT / 32;               // direct loads of a producer for the token tile of a stage
+  const int t0 = blockIdx.x * NT;
   const int nb = blockIdx.y;
   const int r0 = nb * RT_M;
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][NBT];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NBT; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  // ---- loads: producer p fills rows p*32 .. p*32+31 of both tiles, 8 rows per instruction --------
+  // ---- loads: producer p fills rows p*32 .. p*32+31 of the weight tile and its quarter of the token tile, 8 rows
+  // per instruction ----
   const int l_row = lane >> 3;                           // row inside the instruction's 8 rows
   // byte offset of the chunk this lane fetches: row = 8 * instruction + l_row, so (row >> 1) & 7 is
   // (l_row >> 1) for even instructions and (l_row >> 1) ^ 4 for odd ones (ii & 1 below)
   const int l_csw0 = ((lane & 7) ^ (l_row >> 1)) * 16;
   const int l_csw1 = ((lane & 7) ^ (l_row >> 1) ^ 4) * 16;
   const int a_vo = (pw * 32 + l_row) * (K * 2);        // + ii * 8 rows + chunk offset
-  const int b_row = pw * 32 + l_row;                     // + ii * 8
+  const int b_row = pw * (NT / 4) + l_row;               // + ii * 8
   const int n_stages_all = K / RT_K;
   // this workgroup's stages: [s_lo, s_lo + n_stages)
   const int per_z = KSPLIT ? (n_stages_all + (int)gridDim.z - 1) / (int)gridDim.z : n_stages_all;
   const int s_lo = KSPLIT ? (int)blockIdx.z * per_z : 0;
   const int n_stages = KSPLIT ? max(0, min(n_stages_all, s_lo + per_z) - s_lo) : n_stages_all;
   const int q_stages = hd / RT_K, k_stages = kvd / RT_K;
-  const int rows_left = min(max(Tn - t0, 0), RT_N);    // valid token rows of this workgroup
+  const int rows_left = min(max(Tn - t0, 0), NT);      // valid token rows of this workgroup
 
   auto issue = [&](int s_rel, int buf) {
     // (a stage past the last one would get empty descriptors: zeros, no memory access; the loops below
@@ -128,9 +134,9 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
       __amdgpu_buffer_rsrc_t br = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(src + (int64_t)t0 * (rowb / 2) + col), 0, (live && span > 0) ? (int)span : 0, 0x00020000);
 #pragma unroll
-      for (int ii = 0; ii < 4; ++ii)
+      for (int ii = 0; ii < B_LOADS; ++ii)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (pw * 4 + ii) * 1024), 16,
+            br, (lds_ptr_t)(sm.ring + buf * RT_STAGE_B + RT_TILE_B + (pw * B_LOADS + ii) * 1024), 16,
             (b_row + ii * 8) * rowb + ((ii & 1) ? l_csw1 : l_csw0), 0, 0, 0);
     }
   };
@@ -141,7 +147,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
   for (int ks = 0; ks < 4; ++ks) {
     const int pos = ((2 * ks + hi) ^ ((n32 >> 1) & 7)) * 16;
     a_rd[ks] = (wm * 64 + n32) * 128 + pos;
-    b_rd[ks] = RT_TILE_B + (wn * 64 + n32) * 128 + pos;
+    b_rd[ks] = RT_TILE_B + (wn * (NT / 2) + n32) * 128 + pos;
   }
 
   // The fragments of contraction steps 0 and 1 of a stage are requested during the stage before
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
       pre[ks * 4 + 0] = *(const bf16x8*)(base + a_rd[ks]);
       pre[ks * 4 + 1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
       pre[ks * 4 + 2] = *(const bf16x8*)(base + b_rd[ks]);
-      pre[ks * 4 + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
+      if (NBT == 2) pre[ks * 4 + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
     }
   };
   auto compute = [&](int buf, int next_buf) {
@@ -165,31 +171,41 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
       af[ks][0] = pre[ks * 4 + 0];
       af[ks][1] = pre[ks * 4 + 1];
       bfr[ks][0] = pre[ks * 4 + 2];
-      bfr[ks][1] = pre[ks * 4 + 3];
+      if (NBT == 2) bfr[ks][1] = pre[ks * 4 + 3];
     }
 #pragma unroll
     for (int ks = 2; ks < 4; ++ks) {
       af[ks][0] = *(const bf16x8*)(base + a_rd[ks]);
       af[ks][1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
       bfr[ks][0] = *(const bf16x8*)(base + b_rd[ks]);
-      bfr[ks][1] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
+      if (NBT == 2) bfr[ks][1] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
     }
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][0], bfr[ks][0], acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][0], bfr[ks][1], acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][0], acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][1], bfr[ks][1], acc[1][1], 0, 0, 0);
-    }
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < NBT; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][a], bfr[ks][b], acc[a][b], 0, 0, 0);
     // the first fragments of the next stage (in LDS already, see the invariant below): requested behind this stage's
     // last MFMAs, so that they have arrived when the barrier opens (requested after the last MFMA, their latency
     // of a few hundred cycles stood between every two stages: 724 cycles per stage for 512 cycles of MFMAs)
     prefetch(next_buf);
-    // issue order: one of the 16 fragment reads behind each MFMA
+    // issue order: the fragment reads spread evenly behind the MFMAs (16 for 16, or 12 for 8)
+    if (NBT == 2) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int i = 0; i < 16; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
     }
   };
 
@@ -222,7 +238,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
         if (s0 + u < n_stages) {
           // at most stage s+2 may still be in flight; past the end nothing more is issued, and then the
           // count has to drop to zero for stage s+1 to be known complete
-          if (s0 + u + 2 < n_stages) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+          if (s0 + u + 2 < n_stages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 + B_LOADS) : "memory");
           else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           asm volatile("s_barrier" ::: "memory");
           if (s0 + u + RT_STAGES - 1 < n_stages) issue(s0 + u + RT_STAGES - 1, (u + RT_STAGES - 1) % RT_STAGES);
@@ -245,8 +261,8 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     if (!producer) {
       float* zp = zpart + (int64_t)blockIdx.z * Tn * d_R;
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int t = t0 + wn * 64 + b * 32 + n32;
+      for (int b = 0; b < NBT; ++b) {
+        const int t = t0 + wn * (NT / 2) + b * 32 + n32;
         if (t >= Tn) continue;
 #pragma unroll
         for (int a = 0; a < 2; ++a)
@@ -262,7 +278,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NBT; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         // SiLU(z) = z / (1 + 2^(-z log2 e)) with the hardware exp2 and reciprocal (1 ulp each: far inside
@@ -285,9 +301,9 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     __syncthreads();
     // four KV heads at a time: one 16-byte read of the W2 row per accumulator element
     for (int mq = 0; mq < mc && !producer; mq += 4) {
-      float sb[2][4];                              // [token block][KV head of the four]
+      float sb[NBT][4];                            // [token block][KV head of the four]
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NBT; ++b)
 #pragma unroll
         for (int i = 0; i < 4; ++i) sb[b][i] = 0.f;
 #pragma unroll
@@ -297,7 +313,7 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
           const int hh = wm * 64 + a * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
           const float4 w = *(const float4*)&sm.ep.W2s[hh * 32 + mq];
 #pragma unroll
-          for (int b = 0; b < 2; ++b) {
+          for (int b = 0; b < NBT; ++b) {
             sb[b][0] = fmaf(acc[a][b][r], w.x, sb[b][0]);
             sb[b][1] = fmaf(acc[a][b][r], w.y, sb[b][1]);
             sb[b][2] = fmaf(acc[a][b][r], w.z, sb[b][2]);
@@ -305,19 +321,19 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
           }
         }
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NBT; ++b)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float v = sum_across_halves(sb[b][i]);
-          if (hi == 0) sm.ep.red[(wm * RT_N + wn * 64 + b * 32 + n32) * 33 + mq + i] = v;   // columns >= mc: zeros, not read
+          if (hi == 0) sm.ep.red[(wm * NT + wn * (NT / 2) + b * 32 + n32) * 33 + mq + i] = v;   // columns >= mc: zeros, not read
         }
     }
     __syncthreads();
-    for (int i = tid; i < RT_N * mc; i += 512) {
-      int tl = i % RT_N, mm = i / RT_N;
+    for (int i = tid; i < NT * mc; i += 512) {
+      int tl = i % NT, mm = i / NT;
       int t = t0 + tl;
       if (t < Tn)
-        part[((int64_t)nb * h_kv + m0 + mm) * part_T + t] = sm.ep.red[tl * 33 + mm] + sm.ep.red[(RT_N + tl) * 33 + mm];
+        part[((int64_t)nb * h_kv + m0 + mm) * part_T + t] = sm.ep.red[tl * 33 + mm] + sm.ep.red[(NT + tl) * 33 + mm];
     }
   }
 }
@@ -388,33 +404,39 @@ int score_parts_bf16(const Dims& D) {
 }
 
 // Returns the number of partial score tensors written to `part` (the caller sums them): d_R / 128, or 1 when the
-// launch split the contraction (short chunks: at most a quarter as many 128 x 128 tiles as CUs; each slice keeps
-// at least 8 stages; Tuning::score_split: 0 = never, k = k slices).  Measured on 32q/8kv x 128,
-// d_R = 1024: chunks of 1024 tokens (64 tiles, 4 slices) 49 -> 37 us; chunks of 2048 (128 tiles, 2 slices) gained
-// nothing in the head and cost attention 8 % (16 MB of partials through the L2), so two slices are not taken.
+// launch split the contraction (short chunks: at most half as many tiles as CUs; each slice keeps at least 8
+// stages; Tuning::score_split: 0 = never, k = k slices).  Measured on 32q/8kv x 128, d_R = 1024, in microseconds
+// (hot caches): chunks of 2048 tokens 42.4 with 128-token tiles, 37.3 with 64-token tiles, 49.6 with those and two
+// slices; chunks of 1024 tokens 32.9 (128-token tiles, 4 slices), 33.3 (64-token tiles), 29.4 (64-token tiles,
+// 2 slices); chunks of 3072 or 4096 tokens are a third slower with 64-token tiles (more LDS traffic per MFMA).
 int launch_score_bf16(const Dims& D, const void* q, const void* k, const void* v, int T, const void* W1t,
                       const float* W2f, float* part, hipStream_t st, float* zpart, size_t zpart_floats) {
-  dim3 grid((T + RT_N - 1) / RT_N, D.d_R / RT_M);
+  // Token tile: 64 when 128-token tiles would leave at least half of the 256 CUs without one (T <= 2048 at
+  // d_R = 1024).  Tuning::score_nt: 0 = this rule, 64 / 128 = always.
+  const int tiles128 = ((T + 127) / 128) * (D.d_R / RT_M);
+  const int nt = D.tune.score_nt == 64 || D.tune.score_nt == 128 ? D.tune.score_nt : (tiles128 <= 128 ? 64 : 128);
+  dim3 grid((T + nt - 1) / nt, D.d_R / RT_M);
   int n_z = 1;
   if (zpart != nullptr) {
     const int forced = D.tune.score_split;
     const int tiles = (int)(grid.x * grid.y), stages = D.K / RT_K;
-    n_z = forced >= 0 ? forced : (256 / tiles >= 4 ? 256 / tiles : 1);
+    n_z = forced >= 0 ? forced : (256 / tiles >= 2 ? 256 / tiles : 1);
     n_z = n_z > 8 ? 8 : n_z;
     auto last_empty = [&](int n) { return (n - 1) * ((stages + n - 1) / n) >= stages; };   // slices are ceil(stages / n) long
     while (n_z > 1 && ((size_t)n_z * T * D.d_R > zpart_floats || (forced < 0 && stages / n_z < 8) || last_empty(n_z))) --n_z;
     if (n_z < 1) n_z = 1;
   }
+  grid.z = n_z;
+#define LOCRET_SCORE_LAUNCH(KS, NTT)                                                                                  \
+  launch_kernel(score_mfma_kernel<KS, NTT>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,                \
+                (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T,          \
+                KS ? zpart : (float*)nullptr, D.d_R)
   if (n_z == 1) {
-    launch_kernel(score_mfma_kernel<false>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
-                       (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T,
-                       (float*)nullptr, D.d_R);
+    if (nt == 64) LOCRET_SCORE_LAUNCH(false, 64); else LOCRET_SCORE_LAUNCH(false, 128);
     return D.d_R / RT_M;
   }
-  grid.z = n_z;
-  launch_kernel(score_mfma_kernel<true>, grid, dim3(512), 0, st, (const bf16_t*)q, (const bf16_t*)k,
-                     (const bf16_t*)v, T, D.h * D.d, D.h_kv * D.d, (const bf16_t*)W1t, W2f, D.K, D.h_kv, part, T, zpart,
-                     D.d_R);
+  if (nt == 64) LOCRET_SCORE_LAUNCH(true, 64); else LOCRET_SCORE_LAUNCH(true, 128);
+#undef LOCRET_SCORE_LAUNCH
   launch_kernel(score_finish_kernel, dim3(T), dim3(FIN_THREADS), 0, st, (const float*)zpart, n_z, T, D.d_R, W2f,
                      D.h_kv, part, T);
   return 1;

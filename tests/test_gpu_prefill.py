@@ -156,9 +156,22 @@ def test_key_split_chosen_for_short_chunks_behind_a_long_cache():
 
 @pytest.mark.parametrize("n_z", ["0", "2", "5", "8"])
 def test_contraction_split_of_the_retaining_head(n_z, monkeypatch):
-    # short chunks give the retaining head too few 128 x 128 tiles for the CUs; the launcher then slices the
+    # short chunks give the retaining head too few tiles for the CUs; the launcher then slices the
     # contraction and a second kernel sums the slices, applies SiLU and W2 (chosen by itself in most streams of
     # this file).  LOCRET_SCORE_SPLIT (read when the context is created) forces the number of slices, 0 = never.
+    monkeypatch.setenv("LOCRET_SCORE_SPLIT", n_z)
+    for kw in (SMALL[4], SMALL[5], SMALL[6]):
+        w = synth.tiny(**kw)
+        layer, o, _ = _run_stream(w, teacher_forced=True)
+        layer.close()
+
+
+@pytest.mark.parametrize("nt,n_z", [("128", "0"), ("128", "3"), ("64", "0"), ("64", "3")])
+def test_token_tile_of_the_retaining_head_forced(nt, n_z, monkeypatch):
+    # the retaining head takes 64-token tiles for chunks that would leave half of the CUs without a 128-token tile
+    # and 128-token tiles otherwise; LOCRET_SCORE_NT (read when the context is created) forces either, here on
+    # streams with ragged chunk lengths, with and without the contraction split
+    monkeypatch.setenv("LOCRET_SCORE_NT", nt)
     monkeypatch.setenv("LOCRET_SCORE_SPLIT", n_z)
     for kw in (SMALL[4], SMALL[5], SMALL[6]):
         w = synth.tiny(**kw)
