@@ -150,47 +150,32 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     b_rd[ks] = RT_TILE_B + (wn * (NT / 2) + n32) * 128 + pos;
   }
 
-  // The fragments of contraction steps 0 and 1 of a stage are requested during the stage before
-  // (its data is already in LDS then, see the invariant below), so the MFMAs start right behind the barrier.
-  bf16x8 pre[8];
-  auto prefetch = [&](int buf) {
+  // Fragments: two register sets.  While the 16 (or 8) MFMAs of a stage run on one set, the fragments of the whole
+  // next stage (in LDS already, see the invariant below) are requested into the other, one or two reads behind each
+  // MFMA, so every read has a full stage to arrive.  (Measured equal to reading six MFMAs ahead: a computing
+  // wavefront takes about 720 cycles per stage for 512 cycles of MFMAs either way, almost none of them at the
+  // barrier.)
+  constexpr int NFR = 4 * (2 + NBT);             // fragments of a stage: per contraction step 2 of W1, NBT of tokens
+  bf16x8 fr[2][NFR];
+  auto fetch = [&](bf16x8 (&f)[NFR], int buf) {
     const unsigned char* base = sm.ring + buf * RT_STAGE_B;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      pre[ks * 4 + 0] = *(const bf16x8*)(base + a_rd[ks]);
-      pre[ks * 4 + 1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
-      pre[ks * 4 + 2] = *(const bf16x8*)(base + b_rd[ks]);
-      if (NBT == 2) pre[ks * 4 + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
+    for (int ks = 0; ks < 4; ++ks) {
+      f[ks * (2 + NBT) + 0] = *(const bf16x8*)(base + a_rd[ks]);
+      f[ks * (2 + NBT) + 1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
+      f[ks * (2 + NBT) + 2] = *(const bf16x8*)(base + b_rd[ks]);
+      if (NBT == 2) f[ks * (2 + NBT) + 3] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
     }
   };
-  auto compute = [&](int buf, int next_buf) {
-    const unsigned char* base = sm.ring + buf * RT_STAGE_B;
-    bf16x8 af[4][2], bfr[4][2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      af[ks][0] = pre[ks * 4 + 0];
-      af[ks][1] = pre[ks * 4 + 1];
-      bfr[ks][0] = pre[ks * 4 + 2];
-      if (NBT == 2) bfr[ks][1] = pre[ks * 4 + 3];
-    }
-#pragma unroll
-    for (int ks = 2; ks < 4; ++ks) {
-      af[ks][0] = *(const bf16x8*)(base + a_rd[ks]);
-      af[ks][1] = *(const bf16x8*)(base + a_rd[ks] + 32 * 128);
-      bfr[ks][0] = *(const bf16x8*)(base + b_rd[ks]);
-      if (NBT == 2) bfr[ks][1] = *(const bf16x8*)(base + b_rd[ks] + 32 * 128);
-    }
+  auto compute = [&](bf16x8 (&f)[NFR], bf16x8 (&fn)[NFR], int next_buf) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < NBT; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][a], bfr[ks][b], acc[a][b], 0, 0, 0);
-    // the first fragments of the next stage (in LDS already, see the invariant below): requested behind this stage's
-    // last MFMAs, so that they have arrived when the barrier opens (requested after the last MFMA, their latency
-    // of a few hundred cycles stood between every two stages: 724 cycles per stage for 512 cycles of MFMAs)
-    prefetch(next_buf);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks * (2 + NBT) + a], f[ks * (2 + NBT) + 2 + b], acc[a][b], 0, 0, 0);
+    fetch(fn, next_buf);
     // issue order: the fragment reads spread evenly behind the MFMAs (16 for 16, or 12 for 8)
     if (NBT == 2) {
 #pragma unroll
@@ -246,12 +231,12 @@ __global__ __launch_bounds__(512) void score_mfma_kernel(const bf16_t* __restric
     }
   } else {
     asm volatile("s_barrier" ::: "memory");
-    prefetch(0);
+    fetch(fr[0], 0);
     for (int s0 = 0; s0 < n_stages; s0 += RT_STAGES) {
 #pragma unroll
       for (int u = 0; u < RT_STAGES; ++u)
         if (s0 + u < n_stages) {
-          compute(u, (u + 1) % RT_STAGES);     // (behind the last stage the prefetch reads a buffer nobody needs)
+          compute(fr[u & 1], fr[(u + 1) & 1], (u + 1) % RT_STAGES);     // (behind the last stage the fetch reads a buffer nobody needs)
           if (s0 + u + 1 < n_stages) asm volatile("s_barrier" ::: "memory");
         }
     }
