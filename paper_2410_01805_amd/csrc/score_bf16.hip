@@ -4,7 +4,8 @@
 // The hidden pre-activations are formed transposed, H^T[r][t] = W1t[r][:] . x[t][:], with
 // v_mfma_f32_32x32x16_bf16 (A = rows of the transposed weight, B = token rows; both contiguous
 // along the contraction).  A workgroup owns 128 hidden units x 128 tokens (2 x 2 wavefronts of
-// 64 x 64).  The input row is never materialised: each stage of 64 contraction elements lies inside
+// 64 x 64), or x 64 tokens (wavefronts of 64 x 32) for chunks too short to give every CU a 128-token tile.
+// The input row is never materialised: each stage of 64 contraction elements lies inside
 // one of q, k, v and is fetched from that tensor directly.
 //
 // Operand staging goes global -> LDS without passing through registers (buffer_load ... lds,
@@ -17,10 +18,13 @@
 // bytes back to back; bank conflicts are avoided by permuting WHICH 16-byte chunk a lane fetches:
 // position c' of row r holds chunk c' ^ ((r >> 1) & 7), and a fragment read of logical chunk c goes to
 // position c ^ ((r >> 1) & 7): rows are 128 bytes, so even and odd rows already sit in different halves
-// of the 64 banks, and the 8 even (or odd) rows among 16 consecutive ones must take 8 different positions.  Rows past the chunk (t >= T) fall outside the buffer descriptor and arrive
-// as zeros.
+// of the 64 banks, and the 8 even (or odd) rows among 16 consecutive ones must take 8 different positions.
+// Rows past the chunk (t >= T) fall outside the buffer descriptor and arrive as zeros.
+// The computing wavefronts keep two sets of fragment registers: the MFMAs of a stage run on one while
+// the fragments of the next stage are read into the other, one LDS read behind each MFMA.
 //
-// SiLU and the product with W2 run on the accumulators; the workgroup writes its partial score
+// SiLU and the product with W2 run on the accumulators (the W2 rows of the hidden block were fetched by
+// the load wavefronts before the pipeline started); the workgroup writes its partial score
 // part[nb][m][t] (nb = hidden block) and a tiny kernel sums the partials in a fixed order, so the
 // scores are deterministic.
 #include "device_util.h"
