@@ -179,6 +179,18 @@ def test_token_tile_of_the_retaining_head_forced(nt, n_z, monkeypatch):
         layer.close()
 
 
+def test_calls_on_a_stream_of_the_callers():
+    # every launch of a call goes to the stream the caller passes (the binding passes torch's current stream): a
+    # whole teacher-forced stream and the comparisons with the oracle inside a non-default stream
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for kw in (SMALL[0], SMALL[4], SMALL[5]):
+            w = synth.tiny(**kw)
+            layer, o, _ = _run_stream(w, teacher_forced=True)
+            layer.close()
+    stream.synchronize()
+
+
 def test_selection_as_its_own_launch(monkeypatch):
     # by default the head_dim-128 attention launch carries the selection in its first workgroups;
     # LOCRET_FUSE_SELECT=0 (read when the context is created) launches it separately: same kept indices either way
